@@ -1,0 +1,216 @@
+/*
+ * sarathi.h -- C ABI of the hybrid-batch paged attention library for MI355X (gfx950).
+ *
+ * One scheduling iteration of Sarathi-Serve (arXiv 2403.02310) processes a HYBRID BATCH:
+ * every running decode contributes one query token and some prefills contribute a CHUNK
+ * of their prompt (chunked-prefills, section 4.1; stall-free batching, section 4.2,
+ * Algorithm 3).  This library is the attention of one such iteration for one layer:
+ *
+ *   sarathi_build_stall_free_batch   host only: one pass of Algorithm 3
+ *   sarathi_kv_append                write the iteration's new K/V rows into the paged cache
+ *   sarathi_hybrid_attention         softmax attention of every query row of the batch
+ *
+ * Batch description (host arrays of length num_seqs).  Sequence s contributes q_len[s] new
+ * tokens, rows q_start[s] .. q_start[s]+q_len[s]-1 of the batch-ordered tensors
+ * (q_start = exclusive prefix sum of q_len).  ctx_len[s] is its KV length AFTER this
+ * iteration's append, so its new tokens sit at absolute positions
+ * ctx_len[s]-q_len[s] .. ctx_len[s]-1.  q_len == 1 is a decode, q_len > 1 a prefill chunk
+ * on top of a cached prefix of ctx_len-q_len tokens (possibly 0).  Sequences may come in
+ * any order.
+ *
+ * What attention computes (section 2.1): for the query at position p of a sequence, scores
+ * sm_scale * <q, k_i> for i = 0..p (itself included), softmax over them, and the
+ * softmax-weighted average of v_i.  A chunk therefore reads the K/V of all earlier chunks of
+ * its prompt from the cache (section 4.3) plus its own rows causally; chunking changes
+ * nothing in the result.  Query head h reads K/V head h / (num_q_heads/num_kv_heads)
+ * (grouped-query attention, section 2.2).
+ *
+ * Paged cache (section 2.2; page size and in-page layout are this library's choice, the
+ * paper fixes neither).  Position p of sequence s lives in page
+ * block_table[s*max_blocks_per_seq + p/page_size], slot p%page_size.  Elements are bf16:
+ *
+ *   k_cache[((page*num_kv_heads + h)*page_size + slot)*head_dim + c]     slot-major
+ *   v_cache[((page*num_kv_heads + h)*head_dim  + c   )*page_size + slot] channel-major
+ *
+ * (V is stored transposed inside each page so that both contractions read 16-byte runs
+ * along their contraction index straight into matrix-core operands.)  Slots at or beyond
+ * ctx_len and pages not named by a block table are never read in a way that can influence
+ * a result; block-table entries at or beyond ceil(ctx_len/page_size) are never dereferenced.
+ *
+ * Conventions for every function: returns SARATHI_OK (0) or a negative sarathi_status;
+ * never throws, aborts, allocates or frees caller memory.  Device work is enqueued on
+ * `stream` and NOT synchronised; the caller owns every buffer and keeps device buffers
+ * alive until the stream has drained.  "dev" = device pointer, "host" = host pointer.
+ * HOST length arrays may be reused as soon as the call returns.  A handle serves one
+ * stream at a time and is not thread-safe.  Within an iteration call sarathi_kv_append
+ * BEFORE sarathi_hybrid_attention with the same description: attention reads the chunk's
+ * own K/V from the cache.
+ */
+#ifndef SARATHI_H
+#define SARATHI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SARATHI_OK = 0,
+    SARATHI_EINVAL = -1,     /* null pointer, negative size, malformed description */
+    SARATHI_ESHAPE = -2,     /* unsupported head counts / head_dim / page size / dtype */
+    SARATHI_ECAPACITY = -3,  /* exceeds max_tokens / max_seqs / max_blocks_per_seq / max_batch_size / num_pages */
+    SARATHI_EWORKSPACE = -4, /* workspace pointer missing */
+    SARATHI_EHIP = -5        /* a HIP runtime call failed; see sarathi_last_error */
+} sarathi_status;
+
+typedef struct {
+    int32_t num_q_heads;        /* Hq, multiple of num_kv_heads */
+    int32_t num_kv_heads;       /* Hkv */
+    int32_t head_dim;           /* 64 or 128 */
+    int32_t page_size;          /* 16 */
+    int32_t dtype;              /* 0 = bf16 (the only one) */
+    int32_t max_tokens;         /* bound on num_tokens per call */
+    int32_t max_seqs;           /* bound on num_seqs per call */
+    int32_t max_blocks_per_seq; /* row length of block_table */
+} sarathi_config;
+
+typedef struct sarathi_handle sarathi_handle;
+
+/* Creates host-side state (no device work, usable without a GPU for validation and planning).
+ * Pinned staging memory is allocated lazily by the first call that enqueues device work. */
+sarathi_status sarathi_create(const sarathi_config *config, sarathi_handle **out);
+sarathi_status sarathi_destroy(sarathi_handle *handle);
+
+/* Bytes of device scratch the caller must pass as `workspace` (256-byte aligned) to the two
+ * device entry points: batch metadata, the work lists and the split-KV partial results. */
+size_t sarathi_workspace_bytes(const sarathi_handle *handle);
+
+/* Text of the last error on this handle (includes hipGetErrorString where relevant). */
+const char *sarathi_last_error(const sarathi_handle *handle);
+
+/* Tuning knobs, all optional: "split_keys" (target keys per split-KV work item, multiple
+ * of 32, 0 = automatic), "target_items" (work items the automatic choice aims for).
+ * Unknown names return SARATHI_EINVAL. */
+sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);
+
+/*
+ * KV append (section 2.2: keys and values of processed tokens are kept for later iterations).
+ * Copies row t of k_new / v_new, for every token t of the batch, to its page and slot.
+ * Pure data movement: the pool bytes written are exactly the input bytes.
+ *
+ *   k_new, v_new   dev, bf16 [num_tokens, Hkv, head_dim], batch order
+ *   k_cache        dev, bf16 [num_pages, Hkv, page_size, head_dim]   (written)
+ *   v_cache        dev, bf16 [num_pages, Hkv, head_dim, page_size]   (written)
+ *   block_table    dev, int32 [num_seqs, max_blocks_per_seq]
+ *   q_start, q_len, ctx_len   host, int32 [num_seqs]
+ *   num_pages      pages in each pool (64-bit: pools may exceed 2^31 elements)
+ *   workspace      dev, sarathi_workspace_bytes()
+ *   stream         a hipStream_t passed as void* (NULL = the default stream)
+ */
+sarathi_status sarathi_kv_append(sarathi_handle *handle,
+                                 const void *k_new, const void *v_new,
+                                 void *k_cache, void *v_cache,
+                                 const int32_t *block_table,
+                                 const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len,
+                                 int32_t num_seqs, int32_t num_tokens, int64_t num_pages,
+                                 void *workspace, void *stream);
+
+/*
+ * Attention over the hybrid batch (sections 2.1, 4.1-4.3; see the top of this file).
+ *
+ *   q              dev, bf16 [num_tokens, Hq, head_dim], batch order
+ *   k_cache, v_cache, block_table, q_start, q_len, ctx_len, num_pages: as above (read only)
+ *   sm_scale       multiplies every score before the softmax (callers use 1/sqrt(head_dim))
+ *   out            dev, bf16 [num_tokens, Hq, head_dim] (written; fp32 accumulation, one
+ *                  round-to-nearest-even at the end)
+ *
+ * Prefill-chunk rows and decode rows run in the same launch; long key ranges are split
+ * into independent pieces whose partial (max, sum, unnormalised output) triples a second
+ * kernel merges in a fixed order, so results are bitwise reproducible run to run and do
+ * not depend on which physical pages hold the data.
+ */
+sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
+                                        const void *q,
+                                        const void *k_cache, const void *v_cache,
+                                        const int32_t *block_table,
+                                        const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len,
+                                        int32_t num_seqs, int32_t num_tokens, int64_t num_pages,
+                                        float sm_scale, void *out,
+                                        void *workspace, void *stream);
+
+/* Host-only view of the work decomposition sarathi_hybrid_attention would launch for this
+ * description (no device work).  For tests and for sizing studies. */
+typedef struct {
+    int32_t seq;        /* sequence index */
+    int32_t col_begin;  /* first column of the tile; column = row_in_chunk*G + head_in_group */
+    int32_t n_cols;     /* valid columns in the tile */
+    int32_t key_begin;  /* first key position (multiple of 32) */
+    int32_t key_end;    /* one past the last key position this item reads */
+    int32_t part_row;   /* first row of the partial buffers, or -1 if the item writes `out` itself */
+    int32_t kind;       /* 0 = 16-column wave tile */
+    int32_t reserved;
+} sarathi_work_item;
+
+typedef struct {
+    int32_t num_items;        /* work items (each runs once per KV head) */
+    int32_t num_reduce_items; /* tiles whose splits need merging */
+    int32_t num_part_rows;    /* rows of partial results used */
+    int32_t split_keys;       /* keys per split the planner settled on */
+} sarathi_plan_info;
+
+sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *handle,
+                                             const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len,
+                                             int32_t num_seqs, int32_t num_tokens,
+                                             sarathi_plan_info *info,
+                                             sarathi_work_item *items_out, int32_t items_capacity);
+
+/*
+ * Stall-free batching, one iteration (Algorithm 3, section 4.2).  Host only.
+ * Fills the batch in three passes under the token budget: every running decode (one token
+ * each, never dropped), then the next chunk of each running, partially prefilled request,
+ * then waiting requests in the order given while their prompt's pages fit into free_pages.
+ * A prefill receives min(prompt tokens left, chunk_size, token_budget - tokens so far).
+ *
+ * A request with a complete prefill (num_prefilled == prompt_len) that has num_decoded
+ * generated tokens cached enters as a decode with ctx_len = prompt_len + num_decoded + 1.
+ * A prefill enters with q_len = chunk and ctx_len = num_prefilled + chunk.
+ *
+ * out->seq_id, q_start, q_len, ctx_len: caller-allocated host arrays of capacity
+ * max_batch_size.  Order: decodes, running prefills, admitted requests.
+ * Returns SARATHI_ECAPACITY if the running decodes alone exceed max_batch_size.
+ */
+typedef struct {
+    int64_t id;
+    int32_t prompt_len;
+    int32_t num_prefilled;
+    int32_t num_decoded;
+    int32_t reserved;
+} sarathi_request;
+
+typedef struct {
+    int32_t num_seqs;
+    int32_t num_tokens;
+    int32_t num_decodes;
+    int32_t num_prefill_chunks;
+    int32_t num_admitted;     /* how many of waiting_prefills entered (a prefix of that array) */
+    int32_t reserved;
+    int64_t free_pages_left;
+    int64_t *seq_id;
+    int32_t *q_start;
+    int32_t *q_len;
+    int32_t *ctx_len;
+} sarathi_batch;
+
+sarathi_status sarathi_build_stall_free_batch(int32_t token_budget, int32_t chunk_size,
+                                              const sarathi_request *running_decodes, int32_t n_running_decodes,
+                                              const sarathi_request *running_prefills, int32_t n_running_prefills,
+                                              const sarathi_request *waiting_prefills, int32_t n_waiting,
+                                              int64_t free_pages, int32_t page_size, int32_t max_batch_size,
+                                              sarathi_batch *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SARATHI_H */

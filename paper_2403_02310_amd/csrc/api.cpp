@@ -1,0 +1,244 @@
+// Entry points of libsarathi that touch the HIP runtime: handle life cycle, metadata staging,
+// and the enqueue of the kernels.  Everything here is argument checking, planning and
+// bookkeeping; every step of the attention path itself runs in the kernels.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "internal.h"
+
+using namespace sarathi;
+
+namespace {
+constexpr int kStagingSlots = 8;
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+}  // namespace
+
+struct sarathi_handle {
+    sarathi_config cfg;
+    Options opt;
+    WorkspaceLayout ws;
+    std::string err;
+    Plan plan;
+    // Ring of pinned host buffers for the per-call metadata.  A slot is reused only after the
+    // copy that read it has completed (its event), so calls may be enqueued back to back
+    // without the host ever waiting in the steady state.
+    void *staging[kStagingSlots] = {};
+    hipEvent_t staged[kStagingSlots] = {};
+    bool in_flight[kStagingSlots] = {};
+    size_t staging_bytes = 0;
+    int next_slot = 0;
+    bool staging_ready = false;
+};
+
+namespace {
+
+sarathi_status fail(sarathi_handle *h, sarathi_status st, const std::string &msg) {
+    if (h) h->err = msg;
+    return st;
+}
+
+sarathi_status hip_fail(sarathi_handle *h, const char *what, hipError_t e) {
+    return fail(h, SARATHI_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+sarathi_status ensure_staging(sarathi_handle *h) {
+    if (h->staging_ready) return SARATHI_OK;
+    h->staging_bytes = h->ws.part_ml;  // the metadata prefix of the workspace
+    for (int i = 0; i < kStagingSlots; ++i) {
+        hipError_t e = hipHostMalloc(&h->staging[i], h->staging_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) return hip_fail(h, "hipHostMalloc(staging)", e);
+        e = hipEventCreateWithFlags(&h->staged[i], hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(h, "hipEventCreate", e);
+    }
+    h->staging_ready = true;
+    return SARATHI_OK;
+}
+
+sarathi_status acquire_slot(sarathi_handle *h, int *slot) {
+    const int s = h->next_slot;
+    h->next_slot = (s + 1) % kStagingSlots;
+    if (h->in_flight[s]) {
+        hipError_t e = hipEventSynchronize(h->staged[s]);
+        if (e != hipSuccess) return hip_fail(h, "hipEventSynchronize(staging slot)", e);
+        h->in_flight[s] = false;
+    }
+    *slot = s;
+    return SARATHI_OK;
+}
+
+// Packs q_start / q_len / ctx_len at the front of a staging slot; returns bytes used.
+size_t pack_seq_meta(char *dst, const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len, int32_t n) {
+    const size_t bytes = sizeof(int32_t) * (size_t)n;
+    std::memcpy(dst, q_start, bytes);
+    std::memcpy(dst + bytes, q_len, bytes);
+    std::memcpy(dst + 2 * bytes, ctx_len, bytes);
+    return align_up(3 * bytes, 32);
+}
+
+}  // namespace
+
+extern "C" sarathi_status sarathi_create(const sarathi_config *config, sarathi_handle **out) {
+    if (!config || !out) return SARATHI_EINVAL;
+    *out = nullptr;
+    const sarathi_config &c = *config;
+    if (c.num_q_heads < 1 || c.num_kv_heads < 1 || c.max_tokens < 1 || c.max_seqs < 1 || c.max_blocks_per_seq < 1)
+        return SARATHI_EINVAL;
+    if (c.num_q_heads % c.num_kv_heads != 0) return SARATHI_ESHAPE;
+    if (c.head_dim != 64 && c.head_dim != 128) return SARATHI_ESHAPE;
+    if (c.page_size != kPageSize) return SARATHI_ESHAPE;
+    if (c.dtype != 0) return SARATHI_ESHAPE;
+    sarathi_handle *h = new (std::nothrow) sarathi_handle();
+    if (!h) return SARATHI_EINVAL;
+    h->cfg = c;
+    h->ws = make_workspace_layout(c);
+    *out = h;
+    return SARATHI_OK;
+}
+
+extern "C" sarathi_status sarathi_destroy(sarathi_handle *h) {
+    if (!h) return SARATHI_EINVAL;
+    if (h->staging_ready || h->staging[0]) {
+        for (int i = 0; i < kStagingSlots; ++i) {
+            if (h->in_flight[i]) (void)hipEventSynchronize(h->staged[i]);
+            if (h->staged[i]) (void)hipEventDestroy(h->staged[i]);
+            if (h->staging[i]) (void)hipHostFree(h->staging[i]);
+        }
+    }
+    delete h;
+    return SARATHI_OK;
+}
+
+extern "C" size_t sarathi_workspace_bytes(const sarathi_handle *h) { return h ? h->ws.total : 0; }
+
+extern "C" const char *sarathi_last_error(const sarathi_handle *h) { return h ? h->err.c_str() : "null handle"; }
+
+extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name, int64_t value) {
+    if (!h || !name) return SARATHI_EINVAL;
+    if (std::strcmp(name, "split_keys") == 0) {
+        if (value < 0 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "split_keys out of range");
+        h->opt.split_keys = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "target_items") == 0) {
+        if (value < 1 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "target_items out of range");
+        h->opt.target_items = value;
+        return SARATHI_OK;
+    }
+    return fail(h, SARATHI_EINVAL, std::string("unknown option: ") + name);
+}
+
+extern "C" sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *h, const int32_t *q_start, const int32_t *q_len,
+                                                        const int32_t *ctx_len, int32_t num_seqs, int32_t num_tokens,
+                                                        sarathi_plan_info *info, sarathi_work_item *items_out,
+                                                        int32_t items_capacity) {
+    if (!h) return SARATHI_EINVAL;
+    if (!info) return fail(h, SARATHI_EINVAL, "null info");
+    sarathi_status st = validate_batch(h->cfg, q_start, q_len, ctx_len, num_seqs, num_tokens, 1, h->err);
+    if (st != SARATHI_OK) return st;
+    plan_attention(h->cfg, h->opt, h->ws, q_len, ctx_len, num_seqs, h->plan);
+    info->num_items = (int32_t)h->plan.items.size();
+    info->num_reduce_items = (int32_t)h->plan.reduce_items.size();
+    info->num_part_rows = h->plan.num_part_rows;
+    info->split_keys = h->plan.split_keys;
+    if (items_out) {
+        if (items_capacity < info->num_items) return fail(h, SARATHI_ECAPACITY, "items_capacity too small");
+        std::memcpy(items_out, h->plan.items.data(), sizeof(WorkItem) * h->plan.items.size());
+    }
+    return SARATHI_OK;
+}
+
+extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new, const void *v_new, void *k_cache,
+                                            void *v_cache, const int32_t *block_table, const int32_t *q_start,
+                                            const int32_t *q_len, const int32_t *ctx_len, int32_t num_seqs,
+                                            int32_t num_tokens, int64_t num_pages, void *workspace, void *stream) {
+    if (!h) return SARATHI_EINVAL;
+    sarathi_status st = validate_batch(h->cfg, q_start, q_len, ctx_len, num_seqs, num_tokens, num_pages, h->err);
+    if (st != SARATHI_OK) return st;
+    if (num_seqs == 0) return SARATHI_OK;
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_table) return fail(h, SARATHI_EINVAL, "null tensor pointer");
+    if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
+    if ((st = ensure_staging(h)) != SARATHI_OK) return st;
+    int slot;
+    if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
+    char *host = static_cast<char *>(h->staging[slot]);
+    const size_t used = pack_seq_meta(host, q_start, q_len, ctx_len, num_seqs);
+    char *dev = static_cast<char *>(workspace) + h->ws.seq_meta;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
+    e = hipEventRecord(h->staged[slot], s);
+    if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
+    h->in_flight[slot] = true;
+    DeviceBatch b;
+    b.q_start = reinterpret_cast<const int32_t *>(dev);
+    b.q_len = b.q_start + num_seqs;
+    b.ctx_len = b.q_len + num_seqs;
+    b.block_table = block_table;
+    b.max_blocks = h->cfg.max_blocks_per_seq;
+    b.num_seqs = num_seqs;
+    b.num_tokens = num_tokens;
+    e = (hipError_t)launch_kv_append(h->cfg, b, k_new, v_new, k_cache, v_cache, num_pages, stream);
+    if (e != hipSuccess) return hip_fail(h, "launch kv_append", e);
+    return SARATHI_OK;
+}
+
+extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void *q, const void *k_cache,
+                                                   const void *v_cache, const int32_t *block_table,
+                                                   const int32_t *q_start, const int32_t *q_len,
+                                                   const int32_t *ctx_len, int32_t num_seqs, int32_t num_tokens,
+                                                   int64_t num_pages, float sm_scale, void *out, void *workspace,
+                                                   void *stream) {
+    if (!h) return SARATHI_EINVAL;
+    sarathi_status st = validate_batch(h->cfg, q_start, q_len, ctx_len, num_seqs, num_tokens, num_pages, h->err);
+    if (st != SARATHI_OK) return st;
+    if (num_seqs == 0) return SARATHI_OK;
+    if (!q || !k_cache || !v_cache || !block_table || !out) return fail(h, SARATHI_EINVAL, "null tensor pointer");
+    if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale is not finite");
+    if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
+    plan_attention(h->cfg, h->opt, h->ws, q_len, ctx_len, num_seqs, h->plan);
+    if ((st = ensure_staging(h)) != SARATHI_OK) return st;
+    int slot;
+    if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
+
+    // Metadata packed back to back: sequence arrays, work items, reduce items; one copy.
+    char *host = static_cast<char *>(h->staging[slot]);
+    size_t off = pack_seq_meta(host, q_start, q_len, ctx_len, num_seqs);
+    const size_t items_off = off;
+    std::memcpy(host + off, h->plan.items.data(), sizeof(WorkItem) * h->plan.items.size());
+    off = align_up(off + sizeof(WorkItem) * h->plan.items.size(), 32);
+    const size_t reduce_off = off;
+    std::memcpy(host + off, h->plan.reduce_items.data(), sizeof(ReduceItem) * h->plan.reduce_items.size());
+    off += sizeof(ReduceItem) * h->plan.reduce_items.size();
+    if (off > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
+
+    char *ws = static_cast<char *>(workspace);
+    char *dev = ws + h->ws.seq_meta;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(dev, host, off, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
+    e = hipEventRecord(h->staged[slot], s);
+    if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
+    h->in_flight[slot] = true;
+
+    DeviceBatch b;
+    b.q_start = reinterpret_cast<const int32_t *>(dev);
+    b.q_len = b.q_start + num_seqs;
+    b.ctx_len = b.q_len + num_seqs;
+    b.block_table = block_table;
+    b.max_blocks = h->cfg.max_blocks_per_seq;
+    b.num_seqs = num_seqs;
+    b.num_tokens = num_tokens;
+    float *part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
+    float *part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
+    e = (hipError_t)launch_attention(h->cfg, b, q, k_cache, v_cache, num_pages, sm_scale, out,
+                                     reinterpret_cast<const WorkItem *>(dev + items_off),
+                                     (int32_t)h->plan.items.size(), part_ml, part_o, stream);
+    if (e != hipSuccess) return hip_fail(h, "launch attention", e);
+    e = (hipError_t)launch_reduce(h->cfg, b, reinterpret_cast<const ReduceItem *>(dev + reduce_off),
+                                  (int32_t)h->plan.reduce_items.size(), part_ml, part_o, out, stream);
+    if (e != hipSuccess) return hip_fail(h, "launch split-KV reduce", e);
+    return SARATHI_OK;
+}

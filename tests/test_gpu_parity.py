@@ -1,0 +1,155 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 checker, element by element."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from oracle import kv_cache_reference as kvref
+from paper_2403_02310_amd import workloads as wl
+from tests.parity import compare
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hx():
+    from paper_2403_02310_amd import harness
+    return harness
+
+
+def _expected_pools(batch, poison):
+    s = batch.shape
+    kc, vc = kvref.empty_pools(batch.num_pages, s.num_kv_heads, s.head_dim, s.page_size, fill=poison)
+    for i in range(batch.num_seqs):
+        k, v = batch.kv_bits(i)
+        n = int(batch.ctx_len[i])
+        kvref.kv_append(kc, vc, k, v, batch.block_table[i:i + 1], [0], [n], [n])
+    return kc, vc
+
+
+def _check_batch(hx, batch, poison=0x7FC1, check_pools=True):
+    print("case", batch.name, "seed", batch.seed, "q_len", batch.q_len[:8], "ctx", batch.ctx_len[:8], flush=True)
+    st = hx.setup_and_run(batch, poison)
+    got = hx.bf16_tensor_to_f64(st["out"])
+    ref = oracle.attention_for_batch(batch)
+    res = compare(got, ref, batch.name)
+    if check_pools:
+        kc, vc = _expected_pools(batch, poison)
+        np.testing.assert_array_equal(hx.device_to_bits(st["k_cache"]), kc)
+        np.testing.assert_array_equal(hx.device_to_bits(st["v_cache"]), vc)
+    return st, got, ref, res
+
+
+def test_config1_tiny(hx):
+    _check_batch(hx, wl.config1_tiny())
+
+
+@pytest.mark.parametrize("poison", [0x7FC1, 0x7F80, 0xFF80, 0x0000])
+def test_config1_poisoned_pool_does_not_leak(hx, poison):
+    """Unused pages and slots past ctx_len hold NaN / +-inf: outputs stay finite and equal."""
+    _, got, _, _ = _check_batch(hx, wl.config1_tiny(), poison)
+    base = hx.bf16_tensor_to_f64(hx.setup_and_run(wl.config1_tiny(), 0x0000)["out"])
+    np.testing.assert_array_equal(got, base)
+
+
+SHAPES = {
+    "mqa4_d64": wl.AttnShape(4, 1, 64),
+    "gqa4_d128": wl.AttnShape(8, 2, 128),
+    "gqa7_d128": wl.AttnShape(14, 2, 128),
+    "gqa8_d128": wl.AttnShape(16, 2, 128),
+    "mha_d64": wl.AttnShape(3, 3, 64),
+    "mqa20_d128": wl.AttnShape(20, 1, 128),
+}
+
+
+@pytest.mark.parametrize("shape", sorted(SHAPES))
+@pytest.mark.parametrize("seed", [101, 102])
+def test_random_ragged_hybrid(hx, shape, seed):
+    """Odd chunk sizes, mid-page prefixes, 1-token contexts, shuffled sequence order."""
+    b = wl.random_hybrid(seed, SHAPES[shape], n_chunks=3, n_decodes=6, max_chunk=90, max_ctx=420)
+    _check_batch(hx, b)
+
+
+def test_edge_lengths(hx):
+    """Contexts of 1, 15, 16, 17, 31, 32, 33 as decodes and as whole prefills (prefix 0)."""
+    s = wl.AttnShape(8, 2, 128)
+    lens = [1, 15, 16, 17, 31, 32, 33, 64, 65]
+    q_len = [1] * len(lens) + lens
+    ctx = lens + lens
+    b = wl._make("edges", s, q_len, ctx, 77)
+    _check_batch(hx, b)
+
+
+def test_long_decode_uses_splits_and_matches(hx):
+    """A decode long enough to be split, next to short ones; forced small split size too."""
+    s = wl.AttnShape(8, 2, 128)
+    b = wl._make("long_decode", s, [1, 1, 1, 5], [3000, 40, 777, 1500], 78)
+    st, got, ref, _ = _check_batch(hx, b, check_pools=False)
+    info, _ = st["handle"].plan(b.q_start, b.q_len, b.ctx_len)
+    assert info.num_reduce_items > 0
+    h2 = hx.make_handle(b)
+    h2.set_option("split_keys", 64)
+    st2 = hx.setup_and_run(b, 0x7FC1, handle=h2)
+    got2 = hx.bf16_tensor_to_f64(st2["out"])
+    compare(got2, ref, "split64")
+    h3 = hx.make_handle(b)
+    h3.set_option("split_keys", 1 << 20)   # never split
+    st3 = hx.setup_and_run(b, 0x7FC1, handle=h3)
+    compare(hx.bf16_tensor_to_f64(st3["out"]), ref, "nosplit")
+
+
+def test_chunking_invariance_config1(hx):
+    """192-token prompt as 1x192, 3x64, 192x1: KV cache bytes identical, outputs within tolerance of the one fp64 result."""
+    q_all = wl.normal_bf16((1, 0x51, 99), (192, 4, 64))
+    ref = None
+    pools = []
+    for chunk in (192, 64, 1):
+        iters = wl.config1_prompt(chunk)
+        last = iters[-1]
+        k_all, v_all = last.kv_bits(0)
+        if ref is None:
+            ref = oracle.hybrid_attention(q_all, k_all, v_all, [0], [0], [192], [192], last.sm_scale)
+        handle = hx.make_handle(last)
+        k_cache, v_cache = hx.make_pools(last, 0x7FC1)
+        bt = torch.from_numpy(last.block_table).cuda()
+        rows = []
+        for it in iters:
+            n, ctx = int(it.q_len[0]), int(it.ctx_len[0])
+            q_dev = hx.bits_to_device(q_all[ctx - n: ctx])
+            out = hx.run_iteration(handle, it, k_cache, v_cache, bt, q_dev,
+                                   hx.bits_to_device(k_all[ctx - n: ctx]), hx.bits_to_device(v_all[ctx - n: ctx]))
+            rows.append(hx.bf16_tensor_to_f64(out))
+        torch.cuda.synchronize()
+        compare(np.concatenate(rows), ref, "chunk%d" % chunk)
+        pools.append((hx.device_to_bits(k_cache), hx.device_to_bits(v_cache)))
+    for kc, vc in pools[1:]:
+        np.testing.assert_array_equal(kc, pools[0][0])
+        np.testing.assert_array_equal(vc, pools[0][1])
+
+
+def test_block_table_permutation_and_rerun_are_bitwise_stable(hx):
+    """Physical page placement and repetition must not change a single output bit."""
+    b = wl.random_hybrid(5, wl.AttnShape(8, 2, 128), n_chunks=2, n_decodes=4, max_chunk=70, max_ctx=900)
+    a = hx.device_to_bits(hx.setup_and_run(b)["out"])
+    a2 = hx.device_to_bits(hx.setup_and_run(b)["out"])
+    np.testing.assert_array_equal(a, a2)
+    rng = np.random.default_rng(9)
+    perm = rng.permutation(b.num_pages).astype(np.int32)
+    bt2 = np.where(b.block_table >= 0, perm[np.maximum(b.block_table, 0)], -1).astype(np.int32)
+    b2 = wl.HybridBatch(b.name + "_perm", b.shape, b.q_len, b.ctx_len, bt2, b.num_pages, b.seed, b.sm_scale)
+    c = hx.device_to_bits(hx.setup_and_run(b2)["out"])
+    np.testing.assert_array_equal(a, c)
+
+
+def test_empty_batch_is_a_noop(hx):
+    b = wl.config1_tiny()
+    h = hx.make_handle(b)
+    e = np.zeros(0, np.int32)
+    ws = h.ensure_workspace()
+    k_cache, v_cache = hx.make_pools(b, 0)
+    bt = torch.from_numpy(b.block_table).cuda()
+    q = torch.zeros((0, 4, 64), dtype=torch.bfloat16, device="cuda")
+    h.kv_append(q[:, :1], q[:, :1], k_cache, v_cache, bt, e, e, e, num_tokens=0)
+    h.hybrid_attention(q, k_cache, v_cache, bt, e, e, e, 0.125, q, num_tokens=0)
+    torch.cuda.synchronize()
