@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of one iteration's hybrid-batch attention on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic hybrid batch:
+  host:   one pass of stall-free batching (Algorithm 3) producing the batch description
+  device: KV append of the iteration's new rows, attention over the batch, split-KV merge
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c2_chunk|c2_decodes|...]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def make_workload(name: str):
+    from paper_2403_02310_amd import workloads as wl
+    base = name.split("_")[0]
+    full = {"c1": wl.config1_tiny, "c2": wl.config2_mistral_hybrid, "c3": wl.config3_decode_only,
+            "c4": wl.config4_yi_long, "c5": wl.config5_llama70b}[base]()
+    batch = wl.decodes_first(full)
+    if name.endswith("_chunk") or name.endswith("_chunks"):
+        batch = batch.sub_batch([i for i in range(batch.num_seqs) if batch.q_len[i] > 1], name)
+    elif name.endswith("_decodes"):
+        batch = batch.sub_batch([i for i in range(batch.num_seqs) if batch.q_len[i] == 1], name)
+    desc = {
+        "c1": "tiny: 64-token chunk @prefix 128 + 3 decodes (Hq4/Hkv1/d64)",
+        "c2": "Mistral-7B shape (Hq32/Hkv8/d128, page 16): 512-token chunk @prefix U[0,3584] + 64 decodes ctx U[256,4096]",
+        "c3": "Mistral-7B shape: 256 decodes, ctx lognormal(median 1024, sigma 0.8) in [64,8192], pages scattered over 2x100 GB pools",
+        "c4": "Yi-34B shape (Hq56/Hkv8/d128): chunks 1024/512/384 @prefix U[0,12288] + 128 decodes ctx U[1024,16384]",
+        "c5": "LLaMA2-70B shape (Hq64/Hkv8/d128): 2x512-token chunks @prefix U[0,3584] + 1024 decodes ctx U[512,4096]",
+    }[base]
+    if "_" in name:
+        desc += " [" + name.split("_", 1)[1] + " only]"
+    return batch, desc
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--split-keys", type=int, default=0)
+    ap.add_argument("--target-items", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                         "run with --gpus 1\n")
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        return 3
+    torch.cuda.set_device(0)
+    from paper_2403_02310_amd import binding, harness
+
+    batch, desc = make_workload(args.workload)
+    s = batch.shape
+    T, S = batch.num_tokens, batch.num_seqs
+    kv_bytes_per_copy = 2 * batch.num_pages * s.num_kv_heads * s.page_size * s.head_dim * 2
+    copies = args.copies or int(max(1, min(4, (24 << 30) // max(1, kv_bytes_per_copy))))
+
+    # ---- resident inputs --------------------------------------------------------------
+    t_setup = time.time()
+    fill_handle = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=32768, max_seqs=2048,
+                                 max_blocks_per_seq=batch.max_blocks_per_seq)
+    kv_host: dict = {}
+    for i, kv in enumerate(batch.kv_bits_many(range(S), workers=16)):
+        kv_host[i] = kv
+    bt_dev = torch.from_numpy(batch.block_table).cuda()
+    pools = []
+    k0, v0 = harness.make_pools(batch, poison=None)
+    harness.fill_prefixes(fill_handle, batch, k0, v0, bt_dev, kv_host, upto="all")
+    pools.append((k0, v0))
+    for _ in range(copies - 1):
+        pools.append((k0.clone(), v0.clone()))
+    k_new_bits, v_new_bits = harness.new_token_kv(batch, kv_host)
+    k_new, v_new = harness.bits_to_device(k_new_bits), harness.bits_to_device(v_new_bits)
+    qs = [harness.bits_to_device(batch.q_bits(c)) for c in range(copies)]
+    outs = [torch.empty_like(qs[0]) for _ in range(copies)]
+    del fill_handle
+    torch.cuda.synchronize()
+
+    handle = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=max(T, 2048),
+                            max_seqs=max(S, 128), max_blocks_per_seq=batch.max_blocks_per_seq)
+    if args.split_keys:
+        handle.set_option("split_keys", args.split_keys)
+    if args.target_items:
+        handle.set_option("target_items", args.target_items)
+    ws = handle.ensure_workspace()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- scheduler state that yields exactly this batch (decodes first, then the chunks) ----
+    dec = [i for i in range(S) if batch.q_len[i] == 1]
+    pre = [i for i in range(S) if batch.q_len[i] > 1]
+    mk = lambda lst: (binding.Request * max(1, len(lst)))(*lst)
+    running_decodes = mk([binding.Request(i, int(batch.ctx_len[i]) - 1, int(batch.ctx_len[i]) - 1, 0, 0) for i in dec])
+    running_prefills = mk([binding.Request(i, int(batch.ctx_len[i]), int(batch.prefix_len[i]), 0, 0) for i in pre])
+    token_budget = T
+    chunk_size = int(max([batch.q_len[i] for i in pre], default=1))
+    cap = max(S, 1)
+    sb_id = np.zeros(cap, np.int64); sb_qs = np.zeros(cap, np.int32); sb_ql = np.zeros(cap, np.int32); sb_cl = np.zeros(cap, np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    sched_out = binding.Batch()
+    sched_out.seq_id = sb_id.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    sched_out.q_start, sched_out.q_len, sched_out.ctx_len = (a.ctypes.data_as(i32p) for a in (sb_qs, sb_ql, sb_cl))
+    p_qs, p_ql, p_cl = sched_out.q_start, sched_out.q_len, sched_out.ctx_len
+    lib = binding.lib
+    h = handle._h
+    bt_ptr, ws_ptr = bt_dev.data_ptr(), ws.data_ptr()
+    k_new_ptr, v_new_ptr = k_new.data_ptr(), v_new.data_ptr()
+    pool_ptrs = [(k.data_ptr(), v.data_ptr()) for (k, v) in pools]
+    q_ptrs = [q.data_ptr() for q in qs]
+    out_ptrs = [o.data_ptr() for o in outs]
+    num_pages = batch.num_pages
+    sm_scale = float(batch.sm_scale)
+    n_dec, n_pre = len(dec), len(pre)
+
+    def step(i: int) -> None:
+        st = lib.sarathi_build_stall_free_batch(token_budget, chunk_size, running_decodes, n_dec, running_prefills,
+                                                n_pre, None, 0, 0, s.page_size, cap, ctypes.byref(sched_out))
+        if st != 0:
+            raise RuntimeError("scheduler failed: %d" % st)
+        c = i % copies
+        kp, vp = pool_ptrs[c]
+        st = lib.sarathi_kv_append(h, k_new_ptr, v_new_ptr, kp, vp, bt_ptr, p_qs, p_ql, p_cl, sched_out.num_seqs,
+                                   sched_out.num_tokens, num_pages, ws_ptr, stream)
+        if st != 0:
+            raise RuntimeError("kv_append failed: %s" % handle.last_error())
+        st = lib.sarathi_hybrid_attention(h, q_ptrs[c], kp, vp, bt_ptr, p_qs, p_ql, p_cl, sched_out.num_seqs,
+                                          sched_out.num_tokens, num_pages, sm_scale, out_ptrs[c], ws_ptr, stream)
+        if st != 0:
+            raise RuntimeError("hybrid_attention failed: %s" % handle.last_error())
+
+    # the scheduler must reproduce the workload's description exactly
+    step(0)
+    torch.cuda.synchronize()
+    assert sched_out.num_seqs == S and sched_out.num_tokens == T
+    assert (sb_ql[:S] == batch.q_len).all() and (sb_cl[:S] == batch.ctx_len).all() and (sb_qs[:S] == batch.q_start).all()
+    setup_s = time.time() - t_setup
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    if not args.no_kernel_timing:
+        handle.set_option("time_kernels", 1)
+        handle.kernel_times()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kt = handle.kernel_times() if not args.no_kernel_timing else None
+    handle.set_option("time_kernels", 0)
+
+    # host-only cost of a step's CPU side (scheduler + planning), measured separately
+    t2 = time.perf_counter()
+    for i in range(50):
+        lib.sarathi_build_stall_free_batch(token_budget, chunk_size, running_decodes, n_dec, running_prefills, n_pre,
+                                           None, 0, 0, s.page_size, cap, ctypes.byref(sched_out))
+        info = binding.PlanInfo()
+        lib.sarathi_plan_hybrid_attention(h, p_qs, p_ql, p_cl, S, T, ctypes.byref(info), None, 0)
+    host_us = (time.perf_counter() - t2) * 1e6 / 50
+
+    alg_bytes = batch.algorithmic_bytes()
+    alg_flops = batch.algorithmic_flops()
+    result = {
+        "metric": "hybrid-batch attention tokens/s (one iteration: stall-free batch build + KV append + paged GQA attention)",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "iter_us": ms_per_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload + ": " + desc, "num_tokens": T, "num_seqs": S,
+                   "sum_ctx_len": int(batch.ctx_len.astype(np.int64).sum()), "seed": batch.seed,
+                   "kv_copies_rotated": copies, "plan": {"items": info.num_items, "reduce_items": info.num_reduce_items,
+                                                         "split_keys": info.split_keys}},
+        "kv_tokens_per_s": float(batch.ctx_len.astype(np.int64).sum()) / (ms_per_step * 1e-3),
+        "algorithmic_bytes": alg_bytes,
+        "algorithmic_flops": alg_flops,
+        "whole_step": {"GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9, "hbm_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "TFLOPs": alg_flops / (ms_per_step * 1e-3) / 1e12,
+                       "mfma_frac": alg_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "host_us_per_step": host_us,
+        "setup_s": setup_s,
+    }
+    if kt is not None and kt.attention_launches > 0:
+        attn_us = kt.attention_ms * 1e3 / kt.attention_launches
+        result["kernel_us"] = {
+            "attention": attn_us,
+            "reduce": (kt.reduce_ms * 1e3 / kt.reduce_launches) if kt.reduce_launches else 0.0,
+            "kv_append": (kt.append_ms * 1e3 / kt.append_launches) if kt.append_launches else 0.0,
+            "launches": int(kt.attention_launches)}
+        mfma_bound = args.workload.endswith("_chunk") or args.workload.endswith("_chunks")
+        if mfma_bound:
+            ach = alg_flops / (attn_us * 1e-6) / 1e12
+            result["roofline"] = {"bound": "mfma", "kernel": "attn_wave16_kernel", "achieved": ach,
+                                  "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                                  "traffic": None}
+        else:
+            ach = alg_bytes / (attn_us * 1e-6) / 1e9
+            result["roofline"] = {"bound": "hbm", "kernel": "attn_wave16_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
+                                  "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+
+    # ---- CPU baseline: the fp64 checker as it stands, on the host cores, bounded sample ----
+    if not args.no_cpu_baseline:
+        import oracle
+        k_all = np.concatenate([kv_host[i][0] for i in range(S)]); v_all = np.concatenate([kv_host[i][1] for i in range(S)])
+        # aim for ~10-30 s of CPU work: whole batch if small, else a strided sample of batch rows
+        pairs = batch.score_pairs() * s.num_q_heads
+        stride = max(1, int(np.ceil(pairs / 6.0e9)))
+        toks = list(range(0, T, stride))
+        c = (args.steps - 1) % copies
+        tc = time.perf_counter()
+        ref = oracle.hybrid_attention(batch.q_bits(c), k_all, v_all, batch.kv_start, batch.q_start, batch.q_len,
+                                      batch.ctx_len, batch.sm_scale, tokens=toks)
+        cpu_s = time.perf_counter() - tc
+        got = harness.bf16_tensor_to_f64(outs[c])[toks]
+        err = np.abs(got - ref)
+        rel = np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)
+        result["cpu_baseline"] = {"value": len(toks) / cpu_s, "unit": "tokens/s", "cores": oracle.max_threads(),
+                                  "kind": "oracle", "seconds": cpu_s,
+                                  "sample": "every %d-th batch row (%d of %d tokens), all heads" % (stride, len(toks), T)}
+        result["parity_vs_oracle"] = {"max_abs_err": float(err.max()), "max_row_rel_err": float(rel.max()),
+                                      "rows_checked": len(toks)}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

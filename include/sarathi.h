@@ -91,9 +91,20 @@ size_t sarathi_workspace_bytes(const sarathi_handle *handle);
 const char *sarathi_last_error(const sarathi_handle *handle);
 
 /* Tuning knobs, all optional: "split_keys" (target keys per split-KV work item, multiple
- * of 32, 0 = automatic), "target_items" (work items the automatic choice aims for).
+ * of 32, 0 = automatic), "target_items" (work items the automatic choice aims for),
+ * "time_kernels" (0/1, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);
+
+/* Optional instrumentation.  With option "time_kernels" = 1 the library brackets each of its
+ * kernels with a pair of HIP events on the caller's stream (up to 8192 launches per kernel
+ * between two reads).  sarathi_get_kernel_times waits for the recorded events, returns the
+ * summed durations and launch counts since the last read, and resets them. */
+typedef struct {
+    double append_ms, attention_ms, reduce_ms;
+    int64_t append_launches, attention_launches, reduce_launches;
+} sarathi_kernel_times;
+sarathi_status sarathi_get_kernel_times(sarathi_handle *handle, sarathi_kernel_times *out);
 
 /*
  * KV append (section 2.2: keys and values of processed tokens are kept for later iterations).

@@ -54,9 +54,15 @@ class Batch(ctypes.Structure):
                 ("q_len", ctypes.POINTER(ctypes.c_int32)), ("ctx_len", ctypes.POINTER(ctypes.c_int32))]
 
 
+class KernelTimes(ctypes.Structure):
+    _fields_ = [("append_ms", ctypes.c_double), ("attention_ms", ctypes.c_double), ("reduce_ms", ctypes.c_double),
+                ("append_launches", ctypes.c_int64), ("attention_launches", ctypes.c_int64),
+                ("reduce_launches", ctypes.c_int64)]
+
+
 EXPORTED = ["sarathi_create", "sarathi_destroy", "sarathi_workspace_bytes", "sarathi_last_error",
             "sarathi_set_option", "sarathi_kv_append", "sarathi_hybrid_attention",
-            "sarathi_plan_hybrid_attention", "sarathi_build_stall_free_batch"]
+            "sarathi_plan_hybrid_attention", "sarathi_build_stall_free_batch", "sarathi_get_kernel_times"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libsarathi.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -75,6 +81,8 @@ lib.sarathi_last_error.restype = ctypes.c_char_p
 lib.sarathi_last_error.argtypes = [_vp]
 lib.sarathi_set_option.restype = ctypes.c_int
 lib.sarathi_set_option.argtypes = [_vp, ctypes.c_char_p, ctypes.c_int64]
+lib.sarathi_get_kernel_times.restype = ctypes.c_int
+lib.sarathi_get_kernel_times.argtypes = [_vp, ctypes.POINTER(KernelTimes)]
 lib.sarathi_kv_append.restype = ctypes.c_int
 lib.sarathi_kv_append.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32p, _i32p, _i32p,
                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _vp, _vp]
@@ -154,6 +162,11 @@ class Handle:
 
     def set_option(self, name: str, value: int) -> None:
         self._check(lib.sarathi_set_option(self._h, name.encode(), int(value)))
+
+    def kernel_times(self) -> KernelTimes:
+        kt = KernelTimes()
+        self._check(lib.sarathi_get_kernel_times(self._h, ctypes.byref(kt)))
+        return kt
 
     def _check(self, st: int) -> None:
         if st != OK:

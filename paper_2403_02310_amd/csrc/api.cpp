@@ -6,6 +6,8 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <utility>
+#include <vector>
 
 #include "internal.h"
 
@@ -31,6 +33,10 @@ struct sarathi_handle {
     size_t staging_bytes = 0;
     int next_slot = 0;
     bool staging_ready = false;
+    // Optional per-kernel timing: event pairs recorded around each launch.
+    bool time_kernels = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, reduce
+    size_t timing_used[3] = {0, 0, 0};
 };
 
 namespace {
@@ -67,6 +73,28 @@ sarathi_status acquire_slot(sarathi_handle *h, int *slot) {
     }
     *slot = s;
     return SARATHI_OK;
+}
+
+constexpr size_t kMaxTimedLaunches = 8192;
+
+// Records the start event of a timed launch; returns the pair index or -1 when timing is off/full.
+int timing_begin(sarathi_handle *h, int kind, hipStream_t s) {
+    if (!h->time_kernels || h->timing_used[kind] >= kMaxTimedLaunches) return -1;
+    auto &pool = h->timing_pool[kind];
+    if (h->timing_used[kind] == pool.size()) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return -1;
+        if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return -1; }
+        pool.emplace_back(a, b);
+    }
+    const int idx = (int)h->timing_used[kind];
+    if (hipEventRecord(pool[idx].first, s) != hipSuccess) return -1;
+    return idx;
+}
+
+void timing_end(sarathi_handle *h, int kind, int idx, hipStream_t s) {
+    if (idx < 0) return;
+    if (hipEventRecord(h->timing_pool[kind][idx].second, s) == hipSuccess) h->timing_used[kind] = (size_t)idx + 1;
 }
 
 // Packs q_start / q_len / ctx_len at the front of a staging slot; returns bytes used.
@@ -107,6 +135,8 @@ extern "C" sarathi_status sarathi_destroy(sarathi_handle *h) {
             if (h->staging[i]) (void)hipHostFree(h->staging[i]);
         }
     }
+    for (auto &pool : h->timing_pool)
+        for (auto &pr : pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     delete h;
     return SARATHI_OK;
 }
@@ -127,7 +157,33 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.target_items = value;
         return SARATHI_OK;
     }
+    if (std::strcmp(name, "time_kernels") == 0) {
+        h->time_kernels = value != 0;
+        return SARATHI_OK;
+    }
     return fail(h, SARATHI_EINVAL, std::string("unknown option: ") + name);
+}
+
+extern "C" sarathi_status sarathi_get_kernel_times(sarathi_handle *h, sarathi_kernel_times *out) {
+    if (!h || !out) return SARATHI_EINVAL;
+    double ms[3] = {0, 0, 0};
+    int64_t n[3] = {0, 0, 0};
+    for (int kind = 0; kind < 3; ++kind) {
+        for (size_t i = 0; i < h->timing_used[kind]; ++i) {
+            auto &pr = h->timing_pool[kind][i];
+            hipError_t e = hipEventSynchronize(pr.second);
+            if (e != hipSuccess) return hip_fail(h, "hipEventSynchronize(timing)", e);
+            float t = 0.f;
+            e = hipEventElapsedTime(&t, pr.first, pr.second);
+            if (e != hipSuccess) return hip_fail(h, "hipEventElapsedTime", e);
+            ms[kind] += t;
+            n[kind]++;
+        }
+        h->timing_used[kind] = 0;
+    }
+    out->append_ms = ms[0]; out->attention_ms = ms[1]; out->reduce_ms = ms[2];
+    out->append_launches = n[0]; out->attention_launches = n[1]; out->reduce_launches = n[2];
+    return SARATHI_OK;
 }
 
 extern "C" sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *h, const int32_t *q_start, const int32_t *q_len,
@@ -180,7 +236,9 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     b.max_blocks = h->cfg.max_blocks_per_seq;
     b.num_seqs = num_seqs;
     b.num_tokens = num_tokens;
+    const int t0 = timing_begin(h, 0, s);
     e = (hipError_t)launch_kv_append(h->cfg, b, k_new, v_new, k_cache, v_cache, num_pages, stream);
+    timing_end(h, 0, t0, s);
     if (e != hipSuccess) return hip_fail(h, "launch kv_append", e);
     return SARATHI_OK;
 }
@@ -233,12 +291,18 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     b.num_tokens = num_tokens;
     float *part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     float *part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
+    const int t1 = timing_begin(h, 1, s);
     e = (hipError_t)launch_attention(h->cfg, b, q, k_cache, v_cache, num_pages, sm_scale, out,
                                      reinterpret_cast<const WorkItem *>(dev + items_off),
                                      (int32_t)h->plan.items.size(), part_ml, part_o, stream);
+    timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);
-    e = (hipError_t)launch_reduce(h->cfg, b, reinterpret_cast<const ReduceItem *>(dev + reduce_off),
-                                  (int32_t)h->plan.reduce_items.size(), part_ml, part_o, out, stream);
-    if (e != hipSuccess) return hip_fail(h, "launch split-KV reduce", e);
+    if (!h->plan.reduce_items.empty()) {
+        const int t2 = timing_begin(h, 2, s);
+        e = (hipError_t)launch_reduce(h->cfg, b, reinterpret_cast<const ReduceItem *>(dev + reduce_off),
+                                      (int32_t)h->plan.reduce_items.size(), part_ml, part_o, out, stream);
+        timing_end(h, 2, t2, s);
+        if (e != hipSuccess) return hip_fail(h, "launch split-KV reduce", e);
+    }
     return SARATHI_OK;
 }

@@ -180,6 +180,22 @@ class HybridBatch:
                            kv_ids=self.kv_ids[idx])
 
 
+def reorder(batch: HybridBatch, order: Sequence[int], name: Optional[str] = None) -> HybridBatch:
+    """The same batch with its sequences listed in another order (K/V contents follow their sequence)."""
+    idx = np.asarray(list(order), dtype=np.int64)
+    assert sorted(idx.tolist()) == list(range(batch.num_seqs))
+    return HybridBatch(name or batch.name, batch.shape, batch.q_len[idx], batch.ctx_len[idx],
+                       batch.block_table[idx], batch.num_pages, batch.seed, batch.sm_scale,
+                       kv_ids=batch.kv_ids[idx])
+
+
+def decodes_first(batch: HybridBatch) -> HybridBatch:
+    """Algorithm 3's order: every decode, then the prefill chunks (each group in its original order)."""
+    dec = [i for i in range(batch.num_seqs) if batch.q_len[i] == 1]
+    pre = [i for i in range(batch.num_seqs) if batch.q_len[i] != 1]
+    return reorder(batch, dec + pre)
+
+
 def pages_needed(ctx_len: np.ndarray, page_size: int = PAGE_SIZE) -> np.ndarray:
     return (np.asarray(ctx_len, dtype=np.int64) + page_size - 1) // page_size
 
