@@ -90,9 +90,11 @@ size_t sarathi_workspace_bytes(const sarathi_handle *handle);
 /* Text of the last error on this handle (includes hipGetErrorString where relevant). */
 const char *sarathi_last_error(const sarathi_handle *handle);
 
-/* Tuning knobs, all optional: "split_keys" (target keys per split-KV work item, multiple
- * of 32, 0 = automatic), "target_items" (work items the automatic choice aims for),
- * "time_kernels" (0/1, see sarathi_get_kernel_times).
+/* Tuning knobs, all optional: "split_keys" (target keys per split-KV work item of the
+ * 16-column wave tiles, multiple of 32, 0 = automatic), "target_items" (items the automatic
+ * choice aims for), "tile_split_keys" / "tile_target_items" (the same for 128-column chunk
+ * tiles), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
+ * tiles), "time_kernels" (0/1, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);
 
@@ -160,7 +162,7 @@ typedef struct {
     int32_t key_begin;  /* first key position (multiple of 32) */
     int32_t key_end;    /* one past the last key position this item reads */
     int32_t part_row;   /* first row of the partial buffers, or -1 if the item writes `out` itself */
-    int32_t kind;       /* 0 = 16-column wave tile */
+    int32_t kind;       /* 0 = 16-column wave tile (decodes, tiny chunks), 1 = 128-column chunk tile */
     int32_t reserved;
 } sarathi_work_item;
 
@@ -168,7 +170,9 @@ typedef struct {
     int32_t num_items;        /* work items (each runs once per KV head) */
     int32_t num_reduce_items; /* tiles whose splits need merging */
     int32_t num_part_rows;    /* rows of partial results used */
-    int32_t split_keys;       /* keys per split the planner settled on */
+    int32_t split_keys;       /* keys per split the planner settled on for wave tiles */
+    int32_t num_tile_items;   /* the first num_tile_items items are chunk tiles */
+    int32_t tile_split_keys;  /* keys per split for chunk tiles */
 } sarathi_plan_info;
 
 sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *handle,

@@ -38,7 +38,8 @@ class WorkItem(ctypes.Structure):
 
 
 class PlanInfo(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("num_items", "num_reduce_items", "num_part_rows", "split_keys")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("num_items", "num_reduce_items", "num_part_rows", "split_keys",
+                                              "num_tile_items", "tile_split_keys")]
 
 
 class Request(ctypes.Structure):

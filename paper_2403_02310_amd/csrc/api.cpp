@@ -157,6 +157,21 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.target_items = value;
         return SARATHI_OK;
     }
+    if (std::strcmp(name, "tile_split_keys") == 0) {
+        if (value < 0 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "tile_split_keys out of range");
+        h->opt.tile_split_keys = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "tile_target_items") == 0) {
+        if (value < 1 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "tile_target_items out of range");
+        h->opt.tile_target_items = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "tile_min_cols") == 0) {
+        if (value < 1 || value > (1 << 30)) return fail(h, SARATHI_EINVAL, "tile_min_cols out of range");
+        h->opt.tile_min_cols = value;
+        return SARATHI_OK;
+    }
     if (std::strcmp(name, "time_kernels") == 0) {
         h->time_kernels = value != 0;
         return SARATHI_OK;
@@ -199,6 +214,8 @@ extern "C" sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *h, const
     info->num_reduce_items = (int32_t)h->plan.reduce_items.size();
     info->num_part_rows = h->plan.num_part_rows;
     info->split_keys = h->plan.split_keys;
+    info->num_tile_items = h->plan.num_tile_items;
+    info->tile_split_keys = h->plan.tile_split_keys;
     if (items_out) {
         if (items_capacity < info->num_items) return fail(h, SARATHI_ECAPACITY, "items_capacity too small");
         std::memcpy(items_out, h->plan.items.data(), sizeof(WorkItem) * h->plan.items.size());
@@ -293,7 +310,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     float *part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     const int t1 = timing_begin(h, 1, s);
     e = (hipError_t)launch_attention(h->cfg, b, q, k_cache, v_cache, num_pages, sm_scale, out,
-                                     reinterpret_cast<const WorkItem *>(dev + items_off),
+                                     reinterpret_cast<const WorkItem *>(dev + items_off), h->plan.num_tile_items,
                                      (int32_t)h->plan.items.size(), part_ml, part_o, stream);
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);

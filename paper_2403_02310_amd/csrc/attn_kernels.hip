@@ -18,6 +18,24 @@
 // So K, V and Q go from global memory straight into MFMA operands: no LDS, no transposes, no
 // barriers; the softmax is per-lane work plus two cross-lane steps (lanes n, n+16, n+32, n+48).
 //
+// Chunk-tile path (prefill chunks).  A workgroup of four wavefronts owns 128 columns of one
+// sequence (32 per wave) and walks the key range in 32-key tiles staged once per workgroup in
+// LDS (double-buffered, one barrier per tile), so K/V are fetched from L2/HBM once per 128
+// columns instead of once per 16.  The contractions use v_mfma_f32_32x32x16_bf16, again in
+// transposed form with the K rows of a tile permuted (MFMA row 16u+8a+4h+b <-> key 16u+8h+4a+b)
+// so that accumulator lane (h, n) holds, for column n, keys 8h..8h+7 of page u in registers
+// 8u..8u+7: the B operand of the second contraction without any data movement.  K rows are
+// XOR-swizzled in LDS and the two 16-byte halves of a V^T row are swapped on every other group
+// of eight channels, which makes both the staging writes and the operand reads bank-conflict free.
+//
+// Both paths share one launch: a block is either one chunk tile or four independent wave
+// tiles, so the memory-bound decodes fill the machine next to the MFMA-bound chunk tiles (the
+// paper's reason for hybrid batches, section 4.1).
+//
+// The running maximum is only raised when a tile exceeds it by more than 2^8 (the softmax is
+// invariant to the reference point as long as sum and output use the same one), which removes
+// the accumulator rescale from almost every tile.
+//
 // Masking is by select: keys beyond a column's position (causal mask inside a chunk, section
 // 4.1 of the paper) or beyond the item's key range get score -inf; V of slots at or beyond
 // ctx_len is zeroed so that stale cache contents (possibly NaN) cannot reach an accumulator.
@@ -53,10 +71,14 @@ struct AttnParams {
     int32_t num_q_heads;
     int32_t num_kv_heads;
     int32_t group;
-    float scale_log2;  // sm_scale * log2(e): the softmax runs in base 2
+    int32_t num_tile_items;  // items [0, num_tile_items) are 128-column chunk tiles (one block each)
+    int32_t num_items;       // the rest are 16-column wave tiles (four per block)
+    float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
 };
 
 constexpr float kNegSentinel = -1.0e30f;  // finite "no key seen yet" running maximum
+constexpr float kRescaleSlack = 8.0f;     // raise the softmax reference only when exceeded by 2^8
+typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 __device__ __forceinline__ bf16x8 load_bf16x8(const uint16_t *p) {
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
@@ -141,32 +163,33 @@ __device__ __forceinline__ void compute_tile(TileRegs<D> &r, const bf16x8 (&qreg
     float tmax = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(st.m, tmax);
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    if (__any(tmax > st.m + kRescaleSlack)) {  // wave-uniform; rare after the first tiles
+        const float m_new = fmaxf(st.m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+        st.l *= alpha;
+        st.m = m_new;
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) st.o[c] *= alpha;
+    }
     f32x8 p;
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        p[j] = __builtin_amdgcn_exp2f(t[j] - m_new);
+        p[j] = __builtin_amdgcn_exp2f(t[j] - st.m);
         psum += p[j];
     }
-    st.l = st.l * alpha + psum;
-    st.m = m_new;
+    st.l += psum;
     const bf16x8 pT = __builtin_convertvector(p, bf16x8);
 #pragma unroll
-    for (int c = 0; c < D / 16; ++c) {
-        st.o[c] *= alpha;
+    for (int c = 0; c < D / 16; ++c)
         st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.v[c], pT, st.o[c], 0, 0, 0);
-    }
 }
 
 template <int D>
-__global__ __launch_bounds__(64) void attn_wave16_kernel(AttnParams p) {
-    const int lane = threadIdx.x;
+__device__ __forceinline__ void wave16_path(const AttnParams &p, const WorkItem &it, int kvh) {
+    const int lane = threadIdx.x & 63;
     const int n = lane & 15;
     const int g = lane >> 4;
-    const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one item
-    const WorkItem it = p.items[blockIdx.x / p.num_kv_heads];
     const int seq = it.seq;
     const int q_len = p.q_len[seq];
     const int ctx = p.ctx_len[seq];
@@ -248,6 +271,230 @@ __global__ __launch_bounds__(64) void attn_wave16_kernel(AttnParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Chunk-tile path: 4 waves x 32 columns, K/V tiles of 32 keys staged in LDS.
+// ---------------------------------------------------------------------------------------
+template <int D>
+struct ChunkSmem {
+    static constexpr int kKElems = kTileKeys * D;          // K tile: 32 rows of D channels
+    static constexpr int kVElems = 2 * D * kPageSize;      // V tile: two pages of D x 16
+    static constexpr int kBufElems = kKElems + kVElems;
+    static constexpr int kTotalElems = 2 * kBufElems;      // double buffered
+};
+
+// LDS element offset of 16-byte chunk `c` of K row `r` (r = 16*page + slot).
+template <int D>
+__device__ __forceinline__ int k_lds_off(int r, int c) {
+    constexpr int CPR = D / 8;  // chunks per row
+    return (r * CPR + (c ^ (r & (CPR - 1)))) * 8;
+}
+// LDS element offset of the 8-slot half `hh` of V^T row `d` of page `u`.
+template <int D>
+__device__ __forceinline__ int v_lds_off(int u, int d, int hh) {
+    return ((u * D + d) * 2 + (hh ^ ((d >> 3) & 1))) * 8;
+}
+
+template <int D>
+__device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkItem &it, int kvh, uint16_t *smem) {
+    constexpr int NS = D / 16;         // contraction steps of the score MFMAs
+    constexpr int NB = D / 32;         // 32-channel blocks of the output
+    constexpr int PER_THREAD = D / 64; // 16-byte chunks each thread stages per K (and per V) tile
+    constexpr int PAGE_CHUNKS = 2 * D; // 16-byte chunks of one page of one KV head
+    using SM = ChunkSmem<D>;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n = lane & 31;
+    const int h = lane >> 5;
+    const int seq = it.seq;
+    const int q_len = p.q_len[seq];
+    const int ctx = p.ctx_len[seq];
+    const int q_start = p.q_start[seq];
+    const int prefix = ctx - q_len;
+    const int G = p.group;
+
+    // Columns of this wave; lanes (and whole waves) without a valid column shadow the tile's first column.
+    const int wcol = wave * 32 + n;
+    const bool col_valid = wcol < it.n_cols;
+    const int col = it.col_begin + (col_valid ? wcol : 0);
+    const int row = col / G;
+    const int head = kvh * G + (col - row * G);
+    const int pos_eff = min(prefix + row, it.key_end - 1);
+    const int wave_first_col = it.col_begin + ((wave * 32 < it.n_cols) ? wave * 32 : 0);
+    const int min_pos_eff = min(prefix + wave_first_col / G, it.key_end - 1);
+
+    bf16x8 qreg[NS];  // B operand of the score MFMAs: column n, channels 16s + 8h ..
+    {
+        const uint16_t *qp = p.q + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + h * 8;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) qreg[s] = load_bf16x8(qp + s * 16);
+    }
+
+    const int32_t *bt = p.block_table + (int64_t)seq * p.max_blocks;
+    const int n_pages_seq = (ctx + kPageSize - 1) / kPageSize;
+    const int64_t page_stride = (int64_t)p.num_kv_heads * kPageSize * D;
+    const int64_t head_off = (int64_t)kvh * kPageSize * D;
+    const int64_t last_page_id = p.num_pages - 1;
+
+    // Staging: chunk index idx = tid + 256*j of the tile; page u = idx / PAGE_CHUNKS.
+    u32x4 kst[PER_THREAD], vst[PER_THREAD];
+    auto issue_loads = [&](int tile) {
+#pragma unroll
+        for (int j = 0; j < PER_THREAD; ++j) {
+            const int idx = tid + 256 * j;
+            const int u = idx / PAGE_CHUNKS;
+            const int i = idx % PAGE_CHUNKS;
+            int64_t pg = bt[min(tile * 2 + u, n_pages_seq - 1)];
+            pg = pg < 0 ? 0 : (pg > last_page_id ? last_page_id : pg);
+            const int64_t base = pg * page_stride + head_off + (int64_t)i * 8;
+            kst[j] = *reinterpret_cast<const u32x4 *>(p.k_cache + base);
+            vst[j] = *reinterpret_cast<const u32x4 *>(p.v_cache + base);
+        }
+    };
+    auto commit = [&](int tile, int buf) {
+        uint16_t *kb = smem + buf * SM::kBufElems;
+        uint16_t *vb = kb + SM::kKElems;
+        const bool tail = tile * kTileKeys + kTileKeys > ctx;  // tile holds slots at or beyond ctx_len
+#pragma unroll
+        for (int j = 0; j < PER_THREAD; ++j) {
+            const int idx = tid + 256 * j;
+            const int u = idx / PAGE_CHUNKS;
+            const int i = idx % PAGE_CHUNKS;
+            // K: chunk i of the page = slot i/CPR, chunk i%CPR
+            *reinterpret_cast<u32x4 *>(kb + k_lds_off<D>(u * kPageSize + i / (D / 8), i % (D / 8))) = kst[j];
+            // V^T: chunk i of the page = channel i/2, slots 8*(i%2) ..
+            u32x4 v = vst[j];
+            if (tail) {
+                const int key0 = tile * kTileKeys + u * kPageSize + (i & 1) * 8;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    v[w] &= ((key0 + 2 * w < ctx) ? 0x0000FFFFu : 0u) | ((key0 + 2 * w + 1 < ctx) ? 0xFFFF0000u : 0u);
+            }
+            *reinterpret_cast<u32x4 *>(vb + v_lds_off<D>(u, i >> 1, i & 1)) = v;
+        }
+    };
+
+    f32x16 oacc[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
+    float m_ref = kNegSentinel;
+    float l_run = 0.f;
+
+    // MFMA row n of the score tile is key  16u + 8h' + 4a + b  for n = 16u + 8a + 4h' + b.
+    const int k_row = (n & 16) | ((n & 4) << 1) | ((n & 8) >> 1) | (n & 3);
+
+    const int tile_begin = it.key_begin / kTileKeys;
+    const int tile_end = (it.key_end + kTileKeys - 1) / kTileKeys;
+    issue_loads(tile_begin);
+    commit(tile_begin, 0);
+    __syncthreads();
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int buf = (tile - tile_begin) & 1;
+        const bool more = tile + 1 < tile_end;
+        if (more) issue_loads(tile + 1);
+        const uint16_t *kb = smem + buf * SM::kBufElems;
+        const uint16_t *vb = kb + SM::kKElems;
+
+        // S^T = K Q^T
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kb + k_lds_off<D>(k_row, s * 2 + h)));
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], sacc, 0, 0, 0);
+        }
+        // register r of lane (h, n): key  tile*32 + 16*(r/8) + 8h + r%8 , column n
+        const int key0 = tile * kTileKeys + h * 8;
+        float t[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[r] = sacc[r] * p.scale_log2;
+        if (tile * kTileKeys + (kTileKeys - 1) > min_pos_eff) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t[r] = (key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? t[r] : -INFINITY;
+        }
+        float tmax = t[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, t[r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        if (__any(tmax > m_ref + kRescaleSlack)) {
+            const float m_new = fmaxf(m_ref, tmax);
+            const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+            l_run *= alpha;
+            m_ref = m_new;
+#pragma unroll
+            for (int c = 0; c < NB; ++c) oacc[c] *= alpha;
+        }
+        f32x8 p0, p1;
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            p0[j] = __builtin_amdgcn_exp2f(t[j] - m_ref);
+            p1[j] = __builtin_amdgcn_exp2f(t[8 + j] - m_ref);
+            psum += p0[j] + p1[j];
+        }
+        l_run += psum;
+        const bf16x8 pT0 = __builtin_convertvector(p0, bf16x8);
+        const bf16x8 pT1 = __builtin_convertvector(p1, bf16x8);
+        // O^T += V^T P^T
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            const bf16x8 a0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vb + v_lds_off<D>(0, c * 32 + n, h)));
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vb + v_lds_off<D>(1, c * 32 + n, h)));
+            oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pT0, oacc[c], 0, 0, 0);
+            oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pT1, oacc[c], 0, 0, 0);
+        }
+        if (more) commit(tile + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+    const float l = l_run + __shfl_xor(l_run, 32);
+    if (!col_valid) return;
+    // accumulator register r of block c: channel 32c + 8*(r/4) + 4h + r%4
+    if (it.part_row < 0) {
+        const float inv = 1.0f / l;
+        uint16_t *op = p.out + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + h * 4;
+#pragma unroll
+        for (int c = 0; c < NB; ++c)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
+                const bf16x4 o4 = __builtin_convertvector(o * inv, bf16x4);
+                *reinterpret_cast<u32x2 *>(op + c * 32 + q4 * 8) = __builtin_bit_cast(u32x2, o4);
+            }
+    } else {
+        const int64_t prow = ((int64_t)(it.part_row + wcol) * p.num_kv_heads + kvh);
+        float *po = p.part_o + prow * D + h * 4;
+#pragma unroll
+        for (int c = 0; c < NB; ++c)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
+                *reinterpret_cast<f32x4 *>(po + c * 32 + q4 * 8) = o;
+            }
+        if (h == 0) {
+            p.part_ml[prow * 2 + 0] = m_ref;
+            p.part_ml[prow * 2 + 1] = l;
+        }
+    }
+}
+
+// One launch for the whole batch: block = one chunk tile, or four wave tiles.
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
+    const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one item
+    const int blk = blockIdx.x / p.num_kv_heads;
+    if (blk < p.num_tile_items) {
+        chunk_tile_path<D>(p, p.items[blk], kvh, smem);
+    } else {
+        const int idx = p.num_tile_items + (blk - p.num_tile_items) * 4 + (threadIdx.x >> 6);
+        if (idx < p.num_items) wave16_path<D>(p, p.items[idx], kvh);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Split-KV merge: out = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(m_i - max_i m_i), splits
 // taken in index order (fixed order => bitwise reproducible).
 // ---------------------------------------------------------------------------------------
@@ -266,34 +513,35 @@ template <int D>
 __global__ __launch_bounds__(256) void splitkv_reduce_kernel(ReduceParams p) {
     const int kvh = blockIdx.x % p.num_kv_heads;
     const ReduceItem it = p.items[blockIdx.x / p.num_kv_heads];
-    const int c = threadIdx.x >> 4;   // column of the tile handled by this group of 16 threads
     const int d0 = threadIdx.x & 15;  // channels d0, d0+16, ...
-    if (c >= it.n_cols) return;
-    const int col = it.col_begin + c;
-    const int row = col / p.group;
-    const int head = kvh * p.group + (col - row * p.group);
-    float m_max = kNegSentinel;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = (int64_t)(it.part_row + i * it.n_cols + c) * p.num_kv_heads + kvh;
-        m_max = fmaxf(m_max, p.part_ml[prow * 2]);
-    }
-    float acc[D / 16];
+    // a group of 16 threads merges one column at a time
+    for (int c = threadIdx.x >> 4; c < it.n_cols; c += 16) {
+        const int col = it.col_begin + c;
+        const int row = col / p.group;
+        const int head = kvh * p.group + (col - row * p.group);
+        float m_max = kNegSentinel;
+        for (int i = 0; i < it.n_splits; ++i) {
+            const int64_t prow = (int64_t)(it.part_row + i * it.n_cols + c) * p.num_kv_heads + kvh;
+            m_max = fmaxf(m_max, p.part_ml[prow * 2]);
+        }
+        float acc[D / 16];
 #pragma unroll
-    for (int e = 0; e < D / 16; ++e) acc[e] = 0.f;
-    float l = 0.f;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = (int64_t)(it.part_row + i * it.n_cols + c) * p.num_kv_heads + kvh;
-        const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
-        l += w * p.part_ml[prow * 2 + 1];
+        for (int e = 0; e < D / 16; ++e) acc[e] = 0.f;
+        float l = 0.f;
+        for (int i = 0; i < it.n_splits; ++i) {
+            const int64_t prow = (int64_t)(it.part_row + i * it.n_cols + c) * p.num_kv_heads + kvh;
+            const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
+            l += w * p.part_ml[prow * 2 + 1];
 #pragma unroll
-        for (int e = 0; e < D / 16; ++e) acc[e] += w * p.part_o[prow * D + d0 + 16 * e];
-    }
-    const float inv = 1.0f / l;
-    uint16_t *op = p.out + ((int64_t)(p.q_start[it.seq] + row) * p.num_q_heads + head) * D + d0;
+            for (int e = 0; e < D / 16; ++e) acc[e] += w * p.part_o[prow * D + d0 + 16 * e];
+        }
+        const float inv = 1.0f / l;
+        uint16_t *op = p.out + ((int64_t)(p.q_start[it.seq] + row) * p.num_q_heads + head) * D + d0;
 #pragma unroll
-    for (int e = 0; e < D / 16; ++e) {
-        const __bf16 b = (__bf16)(acc[e] * inv);
-        op[16 * e] = __builtin_bit_cast(uint16_t, b);
+        for (int e = 0; e < D / 16; ++e) {
+            const __bf16 b = (__bf16)(acc[e] * inv);
+            op[16 * e] = __builtin_bit_cast(uint16_t, b);
+        }
     }
 }
 
@@ -380,7 +628,7 @@ int launch_kv_append(const sarathi_config &cfg, const DeviceBatch &b, const void
 
 int launch_attention(const sarathi_config &cfg, const DeviceBatch &b, const void *q, const void *k_cache,
                      const void *v_cache, int64_t num_pages, float sm_scale, void *out, const WorkItem *items,
-                     int32_t num_items, float *part_ml, float *part_o, void *stream) {
+                     int32_t num_tile_items, int32_t num_items, float *part_ml, float *part_o, void *stream) {
     if (num_items == 0) return (int)hipSuccess;
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
@@ -399,13 +647,15 @@ int launch_attention(const sarathi_config &cfg, const DeviceBatch &b, const void
     p.num_q_heads = cfg.num_q_heads;
     p.num_kv_heads = cfg.num_kv_heads;
     p.group = cfg.num_q_heads / cfg.num_kv_heads;
+    p.num_tile_items = num_tile_items;
+    p.num_items = num_items;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
-    const unsigned blocks = (unsigned)num_items * (unsigned)cfg.num_kv_heads;
+    const unsigned blocks = (unsigned)(num_tile_items + (num_items - num_tile_items + 3) / 4) * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
-        hipLaunchKernelGGL(attn_wave16_kernel<128>, dim3(blocks), dim3(64), 0, st, p);
+        hipLaunchKernelGGL(attn_hybrid_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(attn_wave16_kernel<64>, dim3(blocks), dim3(64), 0, st, p);
+        hipLaunchKernelGGL(attn_hybrid_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 

@@ -13,7 +13,10 @@ namespace sarathi {
 
 constexpr int kPageSize = 16;     // tokens per page (the only supported value)
 constexpr int kTileKeys = 32;     // keys per inner-loop tile = two pages = one MFMA contraction depth
-constexpr int kWaveCols = 16;     // query columns a wave-tile carries (MFMA N dimension)
+constexpr int kWaveCols = 16;     // query columns a wave tile carries (16x16x32 MFMA N dimension)
+constexpr int kTileCols = 128;    // query columns a chunk tile carries (4 waves x 32x32x16 MFMA N dimension)
+constexpr int kKindWave = 0;      // WorkItem::kind
+constexpr int kKindTile = 1;
 
 // One unit of attention work: a tile of query columns of one sequence against a key range.
 // A "column" is one (query row, query head inside a KV group) pair: col = row*G + head_in_group.
@@ -43,10 +46,12 @@ struct ReduceItem {
 static_assert(sizeof(ReduceItem) == 32, "ReduceItem is copied to the device as raw bytes");
 
 struct Plan {
-    std::vector<WorkItem> items;
+    std::vector<WorkItem> items;          // chunk tiles first (num_tile_items of them), then wave tiles
+    int32_t num_tile_items = 0;
     std::vector<ReduceItem> reduce_items;
     int32_t num_part_rows = 0;
     int32_t split_keys = 0;
+    int32_t tile_split_keys = 0;
 };
 
 // Byte offsets of the regions inside the caller's workspace (all 256-byte aligned).
@@ -64,7 +69,10 @@ struct WorkspaceLayout {
 
 struct Options {
     int64_t split_keys = 0;      // 0 = automatic
-    int64_t target_items = 1536; // automatic choice aims for about this many items per KV head
+    int64_t target_items = 1536; // automatic choice aims for about this many wave items per KV head
+    int64_t tile_split_keys = 0;  // the same two knobs for the 128-column chunk tiles
+    int64_t tile_target_items = 96;
+    int64_t tile_min_cols = 64;   // sequences with fewer columns (q_len*G) use wave tiles only
 };
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg);
@@ -94,7 +102,7 @@ int launch_kv_append(const sarathi_config &cfg, const DeviceBatch &b, const void
 
 int launch_attention(const sarathi_config &cfg, const DeviceBatch &b, const void *q, const void *k_cache,
                      const void *v_cache, int64_t num_pages, float sm_scale, void *out, const WorkItem *items,
-                     int32_t num_items, float *part_ml, float *part_o, void *stream);
+                     int32_t num_tile_items, int32_t num_items, float *part_ml, float *part_o, void *stream);
 
 int launch_reduce(const sarathi_config &cfg, const DeviceBatch &b, const ReduceItem *items, int32_t num_items,
                   const float *part_ml, const float *part_o, void *out, void *stream);
