@@ -58,8 +58,7 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
-    ap.add_argument("--split-keys", type=int, default=0)
-    ap.add_argument("--target-items", type=int, default=0)
+    ap.add_argument("--opt", action="append", default=[], help="library tuning knob name=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -102,10 +101,9 @@ def main() -> int:
 
     handle = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=max(T, 2048),
                             max_seqs=max(S, 128), max_blocks_per_seq=batch.max_blocks_per_seq)
-    if args.split_keys:
-        handle.set_option("split_keys", args.split_keys)
-    if args.target_items:
-        handle.set_option("target_items", args.target_items)
+    for kv in args.opt:
+        name, value = kv.split("=")
+        handle.set_option(name, int(value))
     ws = handle.ensure_workspace()
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -201,8 +199,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload + ": " + desc, "num_tokens": T, "num_seqs": S,
                    "sum_ctx_len": int(batch.ctx_len.astype(np.int64).sum()), "seed": batch.seed,
-                   "kv_copies_rotated": copies, "plan": {"items": info.num_items, "reduce_items": info.num_reduce_items,
-                                                         "split_keys": info.split_keys}},
+                   "kv_copies_rotated": copies, "plan": {"units": info.num_items, "chunk_tile_units": info.num_tile_items,
+                                                         "split_tiles": info.num_reduce_items, "split_keys": info.split_keys,
+                                                         "tile_split_keys": info.tile_split_keys}},
         "kv_tokens_per_s": float(batch.ctx_len.astype(np.int64).sum()) / (ms_per_step * 1e-3),
         "algorithmic_bytes": alg_bytes,
         "algorithmic_flops": alg_flops,
@@ -216,18 +215,17 @@ def main() -> int:
         attn_us = kt.attention_ms * 1e3 / kt.attention_launches
         result["kernel_us"] = {
             "attention": attn_us,
-            "reduce": (kt.reduce_ms * 1e3 / kt.reduce_launches) if kt.reduce_launches else 0.0,
             "kv_append": (kt.append_ms * 1e3 / kt.append_launches) if kt.append_launches else 0.0,
             "launches": int(kt.attention_launches)}
         mfma_bound = args.workload.endswith("_chunk") or args.workload.endswith("_chunks")
         if mfma_bound:
             ach = alg_flops / (attn_us * 1e-6) / 1e12
-            result["roofline"] = {"bound": "mfma", "kernel": "attn_wave16_kernel", "achieved": ach,
+            result["roofline"] = {"bound": "mfma", "kernel": "attn_hybrid_kernel", "achieved": ach,
                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                                   "traffic": None}
         else:
             ach = alg_bytes / (attn_us * 1e-6) / 1e9
-            result["roofline"] = {"bound": "hbm", "kernel": "attn_wave16_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
+            result["roofline"] = {"bound": "hbm", "kernel": "attn_hybrid_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
                                   "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
 
     # ---- CPU baseline: the fp64 checker as it stands, on the host cores, bounded sample ----

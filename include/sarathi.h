@@ -94,7 +94,8 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * 16-column wave tiles, multiple of 32, 0 = automatic), "target_items" (items the automatic
  * choice aims for), "tile_split_keys" / "tile_target_items" (the same for 128-column chunk
  * tiles), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
- * tiles), "time_kernels" (0/1, see sarathi_get_kernel_times).
+ * tiles), "interleave" (0/1: alternate chunk-tile and wave-tile blocks in the launch),
+ * "time_kernels" (0/1, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);
 
@@ -103,8 +104,8 @@ sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int6
  * between two reads).  sarathi_get_kernel_times waits for the recorded events, returns the
  * summed durations and launch counts since the last read, and resets them. */
 typedef struct {
-    double append_ms, attention_ms, reduce_ms;
-    int64_t append_launches, attention_launches, reduce_launches;
+    double append_ms, attention_ms;
+    int64_t append_launches, attention_launches;
 } sarathi_kernel_times;
 sarathi_status sarathi_get_kernel_times(sarathi_handle *handle, sarathi_kernel_times *out);
 
@@ -140,9 +141,12 @@ sarathi_status sarathi_kv_append(sarathi_handle *handle,
  *                  round-to-nearest-even at the end)
  *
  * Prefill-chunk rows and decode rows run in the same launch; long key ranges are split
- * into independent pieces whose partial (max, sum, unnormalised output) triples a second
- * kernel merges in a fixed order, so results are bitwise reproducible run to run and do
- * not depend on which physical pages hold the data.
+ * into independent pieces whose partial (max, sum, unnormalised output) triples are merged
+ * in a fixed order by the piece that finishes last, so results are bitwise reproducible
+ * run to run and do not depend on which physical pages hold the data.  The first call
+ * with a given workspace clears a small counter region inside it with hipMemsetAsync (do
+ * not make that first call inside a stream capture); later calls enqueue only one
+ * host-to-device copy of the batch metadata and one kernel.
  */
 sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
                                         const void *q,
@@ -168,7 +172,7 @@ typedef struct {
 
 typedef struct {
     int32_t num_items;        /* work items (each runs once per KV head) */
-    int32_t num_reduce_items; /* tiles whose splits need merging */
+    int32_t num_reduce_items; /* tiles whose key range was split (their pieces are merged by the last to finish) */
     int32_t num_part_rows;    /* rows of partial results used */
     int32_t split_keys;       /* keys per split the planner settled on for wave tiles */
     int32_t num_tile_items;   /* the first num_tile_items items are chunk tiles */

@@ -56,9 +56,8 @@ class Batch(ctypes.Structure):
 
 
 class KernelTimes(ctypes.Structure):
-    _fields_ = [("append_ms", ctypes.c_double), ("attention_ms", ctypes.c_double), ("reduce_ms", ctypes.c_double),
-                ("append_launches", ctypes.c_int64), ("attention_launches", ctypes.c_int64),
-                ("reduce_launches", ctypes.c_int64)]
+    _fields_ = [("append_ms", ctypes.c_double), ("attention_ms", ctypes.c_double),
+                ("append_launches", ctypes.c_int64), ("attention_launches", ctypes.c_int64)]
 
 
 EXPORTED = ["sarathi_create", "sarathi_destroy", "sarathi_workspace_bytes", "sarathi_last_error",

@@ -3,6 +3,7 @@
 // bookkeeping; every step of the attention path itself runs in the kernels.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <string>
@@ -33,10 +34,12 @@ struct sarathi_handle {
     size_t staging_bytes = 0;
     int next_slot = 0;
     bool staging_ready = false;
+    // Workspace whose arrival counters this handle has zeroed (they stay zero between calls).
+    void *counters_ready_for = nullptr;
     // Optional per-kernel timing: event pairs recorded around each launch.
     bool time_kernels = false;
-    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, reduce
-    size_t timing_used[3] = {0, 0, 0};
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[2];  // append, attention
+    size_t timing_used[2] = {0, 0};
 };
 
 namespace {
@@ -52,7 +55,7 @@ sarathi_status hip_fail(sarathi_handle *h, const char *what, hipError_t e) {
 
 sarathi_status ensure_staging(sarathi_handle *h) {
     if (h->staging_ready) return SARATHI_OK;
-    h->staging_bytes = h->ws.part_ml;  // the metadata prefix of the workspace
+    h->staging_bytes = h->ws.meta_bytes;  // mirrors the metadata region of the workspace
     for (int i = 0; i < kStagingSlots; ++i) {
         hipError_t e = hipHostMalloc(&h->staging[i], h->staging_bytes, hipHostMallocDefault);
         if (e != hipSuccess) return hip_fail(h, "hipHostMalloc(staging)", e);
@@ -97,15 +100,6 @@ void timing_end(sarathi_handle *h, int kind, int idx, hipStream_t s) {
     if (hipEventRecord(h->timing_pool[kind][idx].second, s) == hipSuccess) h->timing_used[kind] = (size_t)idx + 1;
 }
 
-// Packs q_start / q_len / ctx_len at the front of a staging slot; returns bytes used.
-size_t pack_seq_meta(char *dst, const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len, int32_t n) {
-    const size_t bytes = sizeof(int32_t) * (size_t)n;
-    std::memcpy(dst, q_start, bytes);
-    std::memcpy(dst + bytes, q_len, bytes);
-    std::memcpy(dst + 2 * bytes, ctx_len, bytes);
-    return align_up(3 * bytes, 32);
-}
-
 }  // namespace
 
 extern "C" sarathi_status sarathi_create(const sarathi_config *config, sarathi_handle **out) {
@@ -122,6 +116,10 @@ extern "C" sarathi_status sarathi_create(const sarathi_config *config, sarathi_h
     if (!h) return SARATHI_EINVAL;
     h->cfg = c;
     h->ws = make_workspace_layout(c);
+    if (h->ws.max_tiles >= (1 << kUnitTileBits)) {  // tile indices are packed into 22 bits
+        delete h;
+        return SARATHI_ECAPACITY;
+    }
     *out = h;
     return SARATHI_OK;
 }
@@ -172,6 +170,10 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.tile_min_cols = value;
         return SARATHI_OK;
     }
+    if (std::strcmp(name, "interleave") == 0) {
+        h->opt.interleave = value != 0;
+        return SARATHI_OK;
+    }
     if (std::strcmp(name, "time_kernels") == 0) {
         h->time_kernels = value != 0;
         return SARATHI_OK;
@@ -181,9 +183,9 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
 
 extern "C" sarathi_status sarathi_get_kernel_times(sarathi_handle *h, sarathi_kernel_times *out) {
     if (!h || !out) return SARATHI_EINVAL;
-    double ms[3] = {0, 0, 0};
-    int64_t n[3] = {0, 0, 0};
-    for (int kind = 0; kind < 3; ++kind) {
+    double ms[2] = {0, 0};
+    int64_t n[2] = {0, 0};
+    for (int kind = 0; kind < 2; ++kind) {
         for (size_t i = 0; i < h->timing_used[kind]; ++i) {
             auto &pr = h->timing_pool[kind][i];
             hipError_t e = hipEventSynchronize(pr.second);
@@ -196,8 +198,8 @@ extern "C" sarathi_status sarathi_get_kernel_times(sarathi_handle *h, sarathi_ke
         }
         h->timing_used[kind] = 0;
     }
-    out->append_ms = ms[0]; out->attention_ms = ms[1]; out->reduce_ms = ms[2];
-    out->append_launches = n[0]; out->attention_launches = n[1]; out->reduce_launches = n[2];
+    out->append_ms = ms[0]; out->attention_ms = ms[1];
+    out->append_launches = n[0]; out->attention_launches = n[1];
     return SARATHI_OK;
 }
 
@@ -209,16 +211,30 @@ extern "C" sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *h, const
     if (!info) return fail(h, SARATHI_EINVAL, "null info");
     sarathi_status st = validate_batch(h->cfg, q_start, q_len, ctx_len, num_seqs, num_tokens, 1, h->err);
     if (st != SARATHI_OK) return st;
-    plan_attention(h->cfg, h->opt, h->ws, q_len, ctx_len, num_seqs, h->plan);
-    info->num_items = (int32_t)h->plan.items.size();
-    info->num_reduce_items = (int32_t)h->plan.reduce_items.size();
-    info->num_part_rows = h->plan.num_part_rows;
-    info->split_keys = h->plan.split_keys;
-    info->num_tile_items = h->plan.num_tile_items;
-    info->tile_split_keys = h->plan.tile_split_keys;
+    plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
+    const Plan &pl = h->plan;
+    info->num_items = (int32_t)pl.units.size();
+    info->num_reduce_items = pl.num_split_tiles;
+    info->num_part_rows = pl.num_part_rows;
+    info->split_keys = pl.split_keys;
+    info->num_tile_items = pl.num_tile_units;
+    info->tile_split_keys = pl.tile_split_keys;
     if (items_out) {
         if (items_capacity < info->num_items) return fail(h, SARATHI_ECAPACITY, "items_capacity too small");
-        std::memcpy(items_out, h->plan.items.data(), sizeof(WorkItem) * h->plan.items.size());
+        for (size_t i = 0; i < pl.units.size(); ++i) {
+            const uint32_t u = pl.units[i];
+            const TileDesc &t = pl.tiles[u & ((1u << kUnitTileBits) - 1)];
+            const int32_t split = (int32_t)(u >> kUnitTileBits);
+            sarathi_work_item &w = items_out[i];
+            w.seq = t.seq;
+            w.col_begin = t.col_begin;
+            w.n_cols = t.n_cols;
+            w.key_begin = split * t.keys_per_split;
+            w.key_end = std::min(t.n_keys, w.key_begin + t.keys_per_split);
+            w.part_row = t.n_splits > 1 ? t.part_row0 + split * t.n_cols : -1;
+            w.kind = t.kind;
+            w.reserved = 0;
+        }
     }
     return SARATHI_OK;
 }
@@ -236,25 +252,42 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     if ((st = ensure_staging(h)) != SARATHI_OK) return st;
     int slot;
     if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
-    char *host = static_cast<char *>(h->staging[slot]);
-    const size_t used = pack_seq_meta(host, q_start, q_len, ctx_len, num_seqs);
-    char *dev = static_cast<char *>(workspace) + h->ws.seq_meta;
+
+    // Metadata: q_start | q_len | ctx_len | per-block owner of the block's first token.
+    int32_t *host = static_cast<int32_t *>(h->staging[slot]);
+    const size_t n = (size_t)num_seqs;
+    std::memcpy(host, q_start, sizeof(int32_t) * n);
+    std::memcpy(host + n, q_len, sizeof(int32_t) * n);
+    std::memcpy(host + 2 * n, ctx_len, sizeof(int32_t) * n);
+    int32_t *hint = host + 3 * n;
+    const int32_t n_blocks = (num_tokens + kAppendTokensPerBlock - 1) / kAppendTokensPerBlock;
+    for (int32_t b = 0, s = 0; b < n_blocks; ++b) {
+        const int32_t t = b * kAppendTokensPerBlock;
+        while (s + 1 < num_seqs && q_start[s + 1] <= t) ++s;
+        hint[b] = s;
+    }
+    const size_t used = sizeof(int32_t) * (3 * n + (size_t)n_blocks);
+    if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
+
+    char *dev = static_cast<char *>(workspace) + h->ws.meta;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
     e = hipEventRecord(h->staged[slot], s);
     if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
     h->in_flight[slot] = true;
-    DeviceBatch b;
-    b.q_start = reinterpret_cast<const int32_t *>(dev);
-    b.q_len = b.q_start + num_seqs;
-    b.ctx_len = b.q_len + num_seqs;
-    b.block_table = block_table;
-    b.max_blocks = h->cfg.max_blocks_per_seq;
-    b.num_seqs = num_seqs;
-    b.num_tokens = num_tokens;
+
+    AppendMeta m;
+    m.q_start = reinterpret_cast<const int32_t *>(dev);
+    m.q_len = m.q_start + n;
+    m.ctx_len = m.q_len + n;
+    m.block_hint = m.ctx_len + n;
+    m.block_table = block_table;
+    m.max_blocks = h->cfg.max_blocks_per_seq;
+    m.num_seqs = num_seqs;
+    m.num_tokens = num_tokens;
     const int t0 = timing_begin(h, 0, s);
-    e = (hipError_t)launch_kv_append(h->cfg, b, k_new, v_new, k_cache, v_cache, num_pages, stream);
+    e = (hipError_t)launch_kv_append(h->cfg, m, k_new, v_new, k_cache, v_cache, num_pages, stream);
     timing_end(h, 0, t0, s);
     if (e != hipSuccess) return hip_fail(h, "launch kv_append", e);
     return SARATHI_OK;
@@ -273,53 +306,52 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     if (!q || !k_cache || !v_cache || !block_table || !out) return fail(h, SARATHI_EINVAL, "null tensor pointer");
     if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale is not finite");
     if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
-    plan_attention(h->cfg, h->opt, h->ws, q_len, ctx_len, num_seqs, h->plan);
+    plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
+    const Plan &pl = h->plan;
     if ((st = ensure_staging(h)) != SARATHI_OK) return st;
     int slot;
     if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
 
-    // Metadata packed back to back: sequence arrays, work items, reduce items; one copy.
-    char *host = static_cast<char *>(h->staging[slot]);
-    size_t off = pack_seq_meta(host, q_start, q_len, ctx_len, num_seqs);
-    const size_t items_off = off;
-    std::memcpy(host + off, h->plan.items.data(), sizeof(WorkItem) * h->plan.items.size());
-    off = align_up(off + sizeof(WorkItem) * h->plan.items.size(), 32);
-    const size_t reduce_off = off;
-    std::memcpy(host + off, h->plan.reduce_items.data(), sizeof(ReduceItem) * h->plan.reduce_items.size());
-    off += sizeof(ReduceItem) * h->plan.reduce_items.size();
-    if (off > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
-
     char *ws = static_cast<char *>(workspace);
-    char *dev = ws + h->ws.seq_meta;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(dev, host, off, hipMemcpyHostToDevice, s);
+    hipError_t e;
+    if (h->counters_ready_for != workspace) {
+        // First use of this workspace: the arrival counters must start at zero; every launch
+        // leaves them at zero again.
+        e = hipMemsetAsync(ws + h->ws.counters, 0, sizeof(int32_t) * (size_t)h->ws.max_split_tiles * h->cfg.num_kv_heads, s);
+        if (e != hipSuccess) return hip_fail(h, "hipMemsetAsync(counters)", e);
+        h->counters_ready_for = workspace;
+    }
+
+    // Metadata packed back to back: tile descriptors, then work units; one copy.
+    char *host = static_cast<char *>(h->staging[slot]);
+    const size_t tiles_bytes = sizeof(TileDesc) * pl.tiles.size();
+    const size_t units_off = align_up(tiles_bytes, 16);
+    const size_t used = units_off + sizeof(uint32_t) * pl.units.size();
+    if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
+    std::memcpy(host, pl.tiles.data(), tiles_bytes);
+    std::memcpy(host + units_off, pl.units.data(), sizeof(uint32_t) * pl.units.size());
+    char *dev = ws + h->ws.meta;
+    e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
     e = hipEventRecord(h->staged[slot], s);
     if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
     h->in_flight[slot] = true;
 
-    DeviceBatch b;
-    b.q_start = reinterpret_cast<const int32_t *>(dev);
-    b.q_len = b.q_start + num_seqs;
-    b.ctx_len = b.q_len + num_seqs;
-    b.block_table = block_table;
-    b.max_blocks = h->cfg.max_blocks_per_seq;
-    b.num_seqs = num_seqs;
-    b.num_tokens = num_tokens;
-    float *part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
-    float *part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
+    AttnMeta m;
+    m.tiles = reinterpret_cast<const TileDesc *>(dev);
+    m.units = reinterpret_cast<const uint32_t *>(dev + units_off);
+    m.num_tile_units = pl.num_tile_units;
+    m.num_units = (int32_t)pl.units.size();
+    m.interleave = (int32_t)h->opt.interleave;
+    m.block_table = block_table;
+    m.max_blocks = h->cfg.max_blocks_per_seq;
+    m.counters = reinterpret_cast<int32_t *>(ws + h->ws.counters);
+    m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
+    m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     const int t1 = timing_begin(h, 1, s);
-    e = (hipError_t)launch_attention(h->cfg, b, q, k_cache, v_cache, num_pages, sm_scale, out,
-                                     reinterpret_cast<const WorkItem *>(dev + items_off), h->plan.num_tile_items,
-                                     (int32_t)h->plan.items.size(), part_ml, part_o, stream);
+    e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, stream);
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);
-    if (!h->plan.reduce_items.empty()) {
-        const int t2 = timing_begin(h, 2, s);
-        e = (hipError_t)launch_reduce(h->cfg, b, reinterpret_cast<const ReduceItem *>(dev + reduce_off),
-                                      (int32_t)h->plan.reduce_items.size(), part_ml, part_o, out, stream);
-        timing_end(h, 2, t2, s);
-        if (e != hipSuccess) return hip_fail(h, "launch split-KV reduce", e);
-    }
     return SARATHI_OK;
 }

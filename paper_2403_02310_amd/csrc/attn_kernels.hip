@@ -36,6 +36,12 @@
 // invariant to the reference point as long as sum and output use the same one), which removes
 // the accumulator rescale from almost every tile.
 //
+// Split-KV.  A tile whose key range was cut into pieces has every piece write its partial
+// (reference maximum, sum, unnormalised output) triple and bump the tile's arrival counter;
+// the piece that arrives last re-reads all partials in index order, merges them and writes the
+// final rows.  The merge order is fixed, so the result is bitwise reproducible no matter which
+// piece finishes last.  Counters are left at zero for the next call.
+//
 // Masking is by select: keys beyond a column's position (causal mask inside a chunk, section
 // 4.1 of the paper) or beyond the item's key range get score -inf; V of slots at or beyond
 // ctx_len is zeroed so that stale cache contents (possibly NaN) cannot reach an accumulator.
@@ -60,10 +66,9 @@ struct AttnParams {
     const uint16_t *v_cache;
     uint16_t *out;
     const int32_t *block_table;
-    const int32_t *q_start;
-    const int32_t *q_len;
-    const int32_t *ctx_len;
-    const WorkItem *items;
+    const TileDesc *tiles;
+    const uint32_t *units;
+    int32_t *counters;
     float *part_ml;
     float *part_o;
     int64_t num_pages;
@@ -71,10 +76,25 @@ struct AttnParams {
     int32_t num_q_heads;
     int32_t num_kv_heads;
     int32_t group;
-    int32_t num_tile_items;  // items [0, num_tile_items) are 128-column chunk tiles (one block each)
-    int32_t num_items;       // the rest are 16-column wave tiles (four per block)
+    int32_t num_tile_units;  // units [0, num_tile_units) are 128-column chunk tiles (one block each)
+    int32_t num_units;       // the rest are 16-column wave tiles (four per block)
+    int32_t interleave;      // alternate the two kinds of block in the grid
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
 };
+
+// What one work unit (tile, split) covers.
+struct UnitRange {
+    int32_t key_begin;
+    int32_t key_end;   // exclusive
+    int32_t part_row;  // first partial row of this split, or -1: write `out` directly
+};
+__device__ __forceinline__ UnitRange unit_range(const TileDesc &t, int split) {
+    UnitRange r;
+    r.key_begin = split * t.keys_per_split;
+    r.key_end = min(t.n_keys, r.key_begin + t.keys_per_split);
+    r.part_row = t.n_splits > 1 ? t.part_row0 + split * t.n_cols : -1;
+    return r;
+}
 
 constexpr float kNegSentinel = -1.0e30f;  // finite "no key seen yet" running maximum
 constexpr float kRescaleSlack = 8.0f;     // raise the softmax reference only when exceeded by 2^8
@@ -186,24 +206,24 @@ __device__ __forceinline__ void compute_tile(TileRegs<D> &r, const bf16x8 (&qreg
 }
 
 template <int D>
-__device__ __forceinline__ void wave16_path(const AttnParams &p, const WorkItem &it, int kvh) {
+__device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc &it, int split, int kvh) {
     const int lane = threadIdx.x & 63;
     const int n = lane & 15;
     const int g = lane >> 4;
     const int seq = it.seq;
-    const int q_len = p.q_len[seq];
-    const int ctx = p.ctx_len[seq];
-    const int q_start = p.q_start[seq];
-    const int prefix = ctx - q_len;
+    const int ctx = it.ctx_len;
+    const int q_start = it.q_start;
+    const int prefix = ctx - it.q_len;
     const int G = p.group;
+    const UnitRange ur = unit_range(it, split);
 
     // Lanes beyond the tile's valid columns shadow column 0 of the tile and store nothing.
     const bool col_valid = n < it.n_cols;
     const int col = it.col_begin + (col_valid ? n : 0);
     const int row = col / G;
     const int head = kvh * G + (col - row * G);
-    const int pos_eff = min(prefix + row, it.key_end - 1);                 // last key this column may see here
-    const int min_pos_eff = min(prefix + it.col_begin / G, it.key_end - 1);  // the same for the tile's first column
+    const int pos_eff = min(prefix + row, ur.key_end - 1);                 // last key this column may see here
+    const int min_pos_eff = min(prefix + it.col_begin / G, ur.key_end - 1);  // the same for the tile's first column
 
     bf16x8 qreg[D / 32];
     {
@@ -232,8 +252,8 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const WorkItem 
     st.m = kNegSentinel;
     st.l = 0.f;
 
-    const int tile_begin = it.key_begin / kTileKeys;
-    const int tile_end = (it.key_end + kTileKeys - 1) / kTileKeys;
+    const int tile_begin = ur.key_begin / kTileKeys;
+    const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
 
     // Two register sets, ping-pong: the loads of tile i+1 are in flight while tile i computes.
     TileRegs<D> ra, rb;
@@ -249,17 +269,20 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const WorkItem 
 
     float l = st.l + __shfl_xor(st.l, 16);
     l += __shfl_xor(l, 32);
-    if (!col_valid) return;
-    if (it.part_row < 0) {
+    uint16_t *op = p.out + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + g * 4;
+    if (ur.part_row < 0) {
+        if (!col_valid) return;
         const float inv = 1.0f / l;
-        uint16_t *op = p.out + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + g * 4;
 #pragma unroll
         for (int c = 0; c < D / 16; ++c) {
             const bf16x4 o4 = __builtin_convertvector(st.o[c] * inv, bf16x4);
             *reinterpret_cast<u32x2 *>(op + c * 16) = __builtin_bit_cast(u32x2, o4);
         }
-    } else {
-        const int64_t prow = ((int64_t)(it.part_row + n) * p.num_kv_heads + kvh);
+        return;
+    }
+    // Split tile: publish this piece, then the last piece to arrive merges all of them.
+    if (col_valid) {
+        const int64_t prow = ((int64_t)(ur.part_row + n) * p.num_kv_heads + kvh);
         float *po = p.part_o + prow * D + g * 4;
 #pragma unroll
         for (int c = 0; c < D / 16; ++c) *reinterpret_cast<f32x4 *>(po + c * 16) = st.o[c];
@@ -267,6 +290,38 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const WorkItem 
             p.part_ml[prow * 2 + 0] = st.m;
             p.part_ml[prow * 2 + 1] = l;
         }
+    }
+    int32_t *counter = p.counters + (int64_t)it.counter_idx * p.num_kv_heads + kvh;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the whole wave's partial stores before the arrival
+    int arrived = 0;
+    if (lane == 0) arrived = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    arrived = __shfl(arrived, 0);
+    if (arrived != it.n_splits - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other pieces' stores are visible from here on
+    if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+    if (!col_valid) return;
+    float m_max = kNegSentinel;
+    for (int i = 0; i < it.n_splits; ++i) {
+        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + n) * p.num_kv_heads + kvh);
+        m_max = fmaxf(m_max, p.part_ml[prow * 2]);
+    }
+    f32x4 acc[D / 16];
+#pragma unroll
+    for (int c = 0; c < D / 16; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float lsum = 0.f;
+    for (int i = 0; i < it.n_splits; ++i) {
+        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + n) * p.num_kv_heads + kvh);
+        const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
+        lsum += w * p.part_ml[prow * 2 + 1];
+        const float *po = p.part_o + prow * D + g * 4;
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) acc[c] += *reinterpret_cast<const f32x4 *>(po + c * 16) * w;
+    }
+    const float inv = 1.0f / lsum;
+#pragma unroll
+    for (int c = 0; c < D / 16; ++c) {
+        const bf16x4 o4 = __builtin_convertvector(acc[c] * inv, bf16x4);
+        *reinterpret_cast<u32x2 *>(op + c * 16) = __builtin_bit_cast(u32x2, o4);
     }
 }
 
@@ -294,7 +349,8 @@ __device__ __forceinline__ int v_lds_off(int u, int d, int hh) {
 }
 
 template <int D>
-__device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkItem &it, int kvh, uint16_t *smem) {
+__device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileDesc &it, int split, int kvh,
+                                                uint16_t *smem) {
     constexpr int NS = D / 16;         // contraction steps of the score MFMAs
     constexpr int NB = D / 32;         // 32-channel blocks of the output
     constexpr int PER_THREAD = D / 64; // 16-byte chunks each thread stages per K (and per V) tile
@@ -306,11 +362,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkI
     const int n = lane & 31;
     const int h = lane >> 5;
     const int seq = it.seq;
-    const int q_len = p.q_len[seq];
-    const int ctx = p.ctx_len[seq];
-    const int q_start = p.q_start[seq];
-    const int prefix = ctx - q_len;
+    const int ctx = it.ctx_len;
+    const int q_start = it.q_start;
+    const int prefix = ctx - it.q_len;
     const int G = p.group;
+    const UnitRange ur = unit_range(it, split);
 
     // Columns of this wave; lanes (and whole waves) without a valid column shadow the tile's first column.
     const int wcol = wave * 32 + n;
@@ -318,9 +374,9 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkI
     const int col = it.col_begin + (col_valid ? wcol : 0);
     const int row = col / G;
     const int head = kvh * G + (col - row * G);
-    const int pos_eff = min(prefix + row, it.key_end - 1);
+    const int pos_eff = min(prefix + row, ur.key_end - 1);
     const int wave_first_col = it.col_begin + ((wave * 32 < it.n_cols) ? wave * 32 : 0);
-    const int min_pos_eff = min(prefix + wave_first_col / G, it.key_end - 1);
+    const int min_pos_eff = min(prefix + wave_first_col / G, ur.key_end - 1);
 
     bf16x8 qreg[NS];  // B operand of the score MFMAs: column n, channels 16s + 8h ..
     {
@@ -384,8 +440,8 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkI
     // MFMA row n of the score tile is key  16u + 8h' + 4a + b  for n = 16u + 8a + 4h' + b.
     const int k_row = (n & 16) | ((n & 4) << 1) | ((n & 8) >> 1) | (n & 3);
 
-    const int tile_begin = it.key_begin / kTileKeys;
-    const int tile_end = (it.key_end + kTileKeys - 1) / kTileKeys;
+    const int tile_begin = ur.key_begin / kTileKeys;
+    const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
     issue_loads(tile_begin);
     commit(tile_begin, 0);
     __syncthreads();
@@ -450,11 +506,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkI
     }
 
     const float l = l_run + __shfl_xor(l_run, 32);
-    if (!col_valid) return;
     // accumulator register r of block c: channel 32c + 8*(r/4) + 4h + r%4
-    if (it.part_row < 0) {
+    uint16_t *op = p.out + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + h * 4;
+    if (ur.part_row < 0) {
+        if (!col_valid) return;
         const float inv = 1.0f / l;
-        uint16_t *op = p.out + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + h * 4;
 #pragma unroll
         for (int c = 0; c < NB; ++c)
 #pragma unroll
@@ -463,8 +519,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkI
                 const bf16x4 o4 = __builtin_convertvector(o * inv, bf16x4);
                 *reinterpret_cast<u32x2 *>(op + c * 32 + q4 * 8) = __builtin_bit_cast(u32x2, o4);
             }
-    } else {
-        const int64_t prow = ((int64_t)(it.part_row + wcol) * p.num_kv_heads + kvh);
+        return;
+    }
+    // Split tile: publish this piece, then the last piece to arrive merges all of them.
+    if (col_valid) {
+        const int64_t prow = ((int64_t)(ur.part_row + wcol) * p.num_kv_heads + kvh);
         float *po = p.part_o + prow * D + h * 4;
 #pragma unroll
         for (int c = 0; c < NB; ++c)
@@ -478,76 +537,93 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const WorkI
             p.part_ml[prow * 2 + 1] = l;
         }
     }
+    int32_t *counter = p.counters + (int64_t)it.counter_idx * p.num_kv_heads + kvh;
+    int *flag = reinterpret_cast<int *>(smem);  // the tile loop has drained: LDS is free
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    if (tid == 0) *flag = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const int arrived = *flag;
+    if (arrived != it.n_splits - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+    if (!col_valid) return;
+    float m_max = kNegSentinel;
+    for (int i = 0; i < it.n_splits; ++i) {
+        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + wcol) * p.num_kv_heads + kvh);
+        m_max = fmaxf(m_max, p.part_ml[prow * 2]);
+    }
+#pragma unroll
+    for (int c = 0; c < NB; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
+    float lsum = 0.f;
+    for (int i = 0; i < it.n_splits; ++i) {
+        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + wcol) * p.num_kv_heads + kvh);
+        const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
+        lsum += w * p.part_ml[prow * 2 + 1];
+        const float *po = p.part_o + prow * D + h * 4;
+#pragma unroll
+        for (int c = 0; c < NB; ++c)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 o = *reinterpret_cast<const f32x4 *>(po + c * 32 + q4 * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) oacc[c][q4 * 4 + e] += o[e] * w;
+            }
+    }
+    const float inv = 1.0f / lsum;
+#pragma unroll
+    for (int c = 0; c < NB; ++c)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
+            const bf16x4 o4 = __builtin_convertvector(o * inv, bf16x4);
+            *reinterpret_cast<u32x2 *>(op + c * 32 + q4 * 8) = __builtin_bit_cast(u32x2, o4);
+        }
 }
 
-// One launch for the whole batch: block = one chunk tile, or four wave tiles.
+// One launch for the whole batch: block = one chunk-tile unit, or four wave-tile units.
+// With `interleave` the two kinds alternate in the grid so that compute-bound chunk tiles and
+// memory-bound decode waves share compute units instead of running one kind after the other.
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
-    const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one item
+    const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one unit
     const int blk = blockIdx.x / p.num_kv_heads;
-    if (blk < p.num_tile_items) {
-        chunk_tile_path<D>(p, p.items[blk], kvh, smem);
+    const int n_tile_blocks = p.num_tile_units;
+    const int n_wave_blocks = (p.num_units - p.num_tile_units + 3) / 4;
+    int tile_block = -1, wave_block = -1;
+    if (p.interleave) {
+        const int paired = min(n_tile_blocks, n_wave_blocks);
+        if (blk < 2 * paired) {
+            if (blk & 1) wave_block = blk >> 1; else tile_block = blk >> 1;
+        } else if (n_tile_blocks > n_wave_blocks) {
+            tile_block = blk - paired;
+        } else {
+            wave_block = blk - paired;
+        }
     } else {
-        const int idx = p.num_tile_items + (blk - p.num_tile_items) * 4 + (threadIdx.x >> 6);
-        if (idx < p.num_items) wave16_path<D>(p, p.items[idx], kvh);
+        if (blk < n_tile_blocks) tile_block = blk; else wave_block = blk - n_tile_blocks;
     }
-}
-
-// ---------------------------------------------------------------------------------------
-// Split-KV merge: out = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(m_i - max_i m_i), splits
-// taken in index order (fixed order => bitwise reproducible).
-// ---------------------------------------------------------------------------------------
-struct ReduceParams {
-    const ReduceItem *items;
-    const float *part_ml;
-    const float *part_o;
-    uint16_t *out;
-    const int32_t *q_start;
-    int32_t num_q_heads;
-    int32_t num_kv_heads;
-    int32_t group;
-};
-
-template <int D>
-__global__ __launch_bounds__(256) void splitkv_reduce_kernel(ReduceParams p) {
-    const int kvh = blockIdx.x % p.num_kv_heads;
-    const ReduceItem it = p.items[blockIdx.x / p.num_kv_heads];
-    const int d0 = threadIdx.x & 15;  // channels d0, d0+16, ...
-    // a group of 16 threads merges one column at a time
-    for (int c = threadIdx.x >> 4; c < it.n_cols; c += 16) {
-        const int col = it.col_begin + c;
-        const int row = col / p.group;
-        const int head = kvh * p.group + (col - row * p.group);
-        float m_max = kNegSentinel;
-        for (int i = 0; i < it.n_splits; ++i) {
-            const int64_t prow = (int64_t)(it.part_row + i * it.n_cols + c) * p.num_kv_heads + kvh;
-            m_max = fmaxf(m_max, p.part_ml[prow * 2]);
-        }
-        float acc[D / 16];
-#pragma unroll
-        for (int e = 0; e < D / 16; ++e) acc[e] = 0.f;
-        float l = 0.f;
-        for (int i = 0; i < it.n_splits; ++i) {
-            const int64_t prow = (int64_t)(it.part_row + i * it.n_cols + c) * p.num_kv_heads + kvh;
-            const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
-            l += w * p.part_ml[prow * 2 + 1];
-#pragma unroll
-            for (int e = 0; e < D / 16; ++e) acc[e] += w * p.part_o[prow * D + d0 + 16 * e];
-        }
-        const float inv = 1.0f / l;
-        uint16_t *op = p.out + ((int64_t)(p.q_start[it.seq] + row) * p.num_q_heads + head) * D + d0;
-#pragma unroll
-        for (int e = 0; e < D / 16; ++e) {
-            const __bf16 b = (__bf16)(acc[e] * inv);
-            op[16 * e] = __builtin_bit_cast(uint16_t, b);
+    constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
+    if (tile_block >= 0) {
+        const uint32_t u = p.units[tile_block];
+        chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
+    } else {
+        const int idx = p.num_tile_units + wave_block * 4 + (threadIdx.x >> 6);
+        if (idx < p.num_units) {
+            const uint32_t u = p.units[idx];
+            wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// KV append: byte copies into the paged pools.  One thread moves 8 channels of one
-// (token, KV head): a 16-byte K store and eight 2-byte V stores (V pages are channel-major).
+// KV append: byte copies into the paged pools.  A block moves kAppendTokensPerBlock tokens;
+// one thread-step moves 8 channels of one (token, KV head): a 16-byte K store and eight 2-byte
+// V stores (V pages are channel-major).  The host supplies, per block, the sequence that owns
+// the block's first token, so a thread finds its sequence by walking forward a few entries.
 // ---------------------------------------------------------------------------------------
 struct AppendParams {
     const uint16_t *k_new;
@@ -558,125 +634,106 @@ struct AppendParams {
     const int32_t *q_start;
     const int32_t *q_len;
     const int32_t *ctx_len;
+    const int32_t *block_hint;
     int64_t num_pages;
-    int64_t total_threads;
     int32_t max_blocks;
     int32_t num_seqs;
+    int32_t num_tokens;
     int32_t num_kv_heads;
 };
 
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(AppendParams p) {
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= p.total_threads) return;
     constexpr int kChunks = D / 8;
-    const int chunk = (int)(tid % kChunks);
-    const int h = (int)((tid / kChunks) % p.num_kv_heads);
-    const int t = (int)(tid / ((int64_t)kChunks * p.num_kv_heads));
-    // owning sequence: last s with q_start[s] <= t
-    int lo = 0, hi = p.num_seqs - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (p.q_start[mid] <= t) lo = mid; else hi = mid - 1;
-    }
-    const int s = lo;
-    const int pos = p.ctx_len[s] - p.q_len[s] + (t - p.q_start[s]);
-    int64_t page = p.block_table[(int64_t)s * p.max_blocks + pos / kPageSize];
-    if (page < 0 || page >= p.num_pages) return;  // a corrupt table entry must not become a wild store
-    const int slot = pos % kPageSize;
-    const int64_t src = ((int64_t)t * p.num_kv_heads + h) * D + chunk * 8;
-    const u32x4 kv = *reinterpret_cast<const u32x4 *>(p.k_new + src);
-    const u32x4 vv = *reinterpret_cast<const u32x4 *>(p.v_new + src);
-    const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
-    *reinterpret_cast<u32x4 *>(p.k_cache + head_base + slot * D + chunk * 8) = kv;
-    uint16_t *vdst = p.v_cache + head_base + (int64_t)(chunk * 8) * kPageSize + slot;
+    const int per_token = kChunks * p.num_kv_heads;
+    const int t0 = blockIdx.x * kAppendTokensPerBlock;
+    const int t1 = min(p.num_tokens, t0 + kAppendTokensPerBlock);
+    const int hint = p.block_hint[blockIdx.x];
+    for (int w = threadIdx.x; w < (t1 - t0) * per_token; w += blockDim.x) {
+        const int t = t0 + w / per_token;
+        const int r = w % per_token;
+        const int h = r / kChunks;
+        const int chunk = r % kChunks;
+        int s = hint;
+        while (s + 1 < p.num_seqs && p.q_start[s + 1] <= t) ++s;  // at most kAppendTokensPerBlock steps
+        const int pos = p.ctx_len[s] - p.q_len[s] + (t - p.q_start[s]);
+        const int64_t page = p.block_table[(int64_t)s * p.max_blocks + pos / kPageSize];
+        if (page < 0 || page >= p.num_pages) continue;  // a corrupt table entry must not become a wild store
+        const int slot = pos % kPageSize;
+        const int64_t src = ((int64_t)t * p.num_kv_heads + h) * D + chunk * 8;
+        const u32x4 kv = *reinterpret_cast<const u32x4 *>(p.k_new + src);
+        const u32x4 vv = *reinterpret_cast<const u32x4 *>(p.v_new + src);
+        const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
+        *reinterpret_cast<u32x4 *>(p.k_cache + head_base + slot * D + chunk * 8) = kv;
+        uint16_t *vdst = p.v_cache + head_base + (int64_t)(chunk * 8) * kPageSize + slot;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint32_t word = vv[e >> 1];
-        vdst[e * kPageSize] = (uint16_t)((e & 1) ? (word >> 16) : (word & 0xFFFFu));
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t word = vv[e >> 1];
+            vdst[e * kPageSize] = (uint16_t)((e & 1) ? (word >> 16) : (word & 0xFFFFu));
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
-int launch_kv_append(const sarathi_config &cfg, const DeviceBatch &b, const void *k_new, const void *v_new,
+int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void *k_new, const void *v_new,
                      void *k_cache, void *v_cache, int64_t num_pages, void *stream) {
+    if (m.num_tokens == 0) return (int)hipSuccess;
     AppendParams p;
     p.k_new = static_cast<const uint16_t *>(k_new);
     p.v_new = static_cast<const uint16_t *>(v_new);
     p.k_cache = static_cast<uint16_t *>(k_cache);
     p.v_cache = static_cast<uint16_t *>(v_cache);
-    p.block_table = b.block_table;
-    p.q_start = b.q_start;
-    p.q_len = b.q_len;
-    p.ctx_len = b.ctx_len;
+    p.block_table = m.block_table;
+    p.q_start = m.q_start;
+    p.q_len = m.q_len;
+    p.ctx_len = m.ctx_len;
+    p.block_hint = m.block_hint;
     p.num_pages = num_pages;
-    p.max_blocks = b.max_blocks;
-    p.num_seqs = b.num_seqs;
+    p.max_blocks = m.max_blocks;
+    p.num_seqs = m.num_seqs;
+    p.num_tokens = m.num_tokens;
     p.num_kv_heads = cfg.num_kv_heads;
-    p.total_threads = (int64_t)b.num_tokens * cfg.num_kv_heads * (cfg.head_dim / 8);
-    const int64_t blocks = (p.total_threads + 255) / 256;
-    if (blocks == 0) return (int)hipSuccess;
+    const unsigned blocks = (unsigned)((m.num_tokens + kAppendTokensPerBlock - 1) / kAppendTokensPerBlock);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
-        hipLaunchKernelGGL(kv_append_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(kv_append_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(kv_append_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(kv_append_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 
-int launch_attention(const sarathi_config &cfg, const DeviceBatch &b, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, const WorkItem *items,
-                     int32_t num_tile_items, int32_t num_items, float *part_ml, float *part_o, void *stream) {
-    if (num_items == 0) return (int)hipSuccess;
+int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, void *stream) {
+    if (m.num_units == 0) return (int)hipSuccess;
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
     p.k_cache = static_cast<const uint16_t *>(k_cache);
     p.v_cache = static_cast<const uint16_t *>(v_cache);
     p.out = static_cast<uint16_t *>(out);
-    p.block_table = b.block_table;
-    p.q_start = b.q_start;
-    p.q_len = b.q_len;
-    p.ctx_len = b.ctx_len;
-    p.items = items;
-    p.part_ml = part_ml;
-    p.part_o = part_o;
+    p.block_table = m.block_table;
+    p.tiles = m.tiles;
+    p.units = m.units;
+    p.counters = m.counters;
+    p.part_ml = m.part_ml;
+    p.part_o = m.part_o;
     p.num_pages = num_pages;
-    p.max_blocks = b.max_blocks;
+    p.max_blocks = m.max_blocks;
     p.num_q_heads = cfg.num_q_heads;
     p.num_kv_heads = cfg.num_kv_heads;
     p.group = cfg.num_q_heads / cfg.num_kv_heads;
-    p.num_tile_items = num_tile_items;
-    p.num_items = num_items;
+    p.num_tile_units = m.num_tile_units;
+    p.num_units = m.num_units;
+    p.interleave = m.interleave;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
-    const unsigned blocks = (unsigned)(num_tile_items + (num_items - num_tile_items + 3) / 4) * (unsigned)cfg.num_kv_heads;
+    const unsigned blocks =
+        (unsigned)(m.num_tile_units + (m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
         hipLaunchKernelGGL(attn_hybrid_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
     else
         hipLaunchKernelGGL(attn_hybrid_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
-    return (int)hipGetLastError();
-}
-
-int launch_reduce(const sarathi_config &cfg, const DeviceBatch &b, const ReduceItem *items, int32_t num_items,
-                  const float *part_ml, const float *part_o, void *out, void *stream) {
-    if (num_items == 0) return (int)hipSuccess;
-    ReduceParams p;
-    p.items = items;
-    p.part_ml = part_ml;
-    p.part_o = part_o;
-    p.out = static_cast<uint16_t *>(out);
-    p.q_start = b.q_start;
-    p.num_q_heads = cfg.num_q_heads;
-    p.num_kv_heads = cfg.num_kv_heads;
-    p.group = cfg.num_q_heads / cfg.num_kv_heads;
-    const unsigned blocks = (unsigned)num_items * (unsigned)cfg.num_kv_heads;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (cfg.head_dim == 128)
-        hipLaunchKernelGGL(splitkv_reduce_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL(splitkv_reduce_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 

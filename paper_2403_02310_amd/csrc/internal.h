@@ -15,40 +15,40 @@ constexpr int kPageSize = 16;     // tokens per page (the only supported value)
 constexpr int kTileKeys = 32;     // keys per inner-loop tile = two pages = one MFMA contraction depth
 constexpr int kWaveCols = 16;     // query columns a wave tile carries (16x16x32 MFMA N dimension)
 constexpr int kTileCols = 128;    // query columns a chunk tile carries (4 waves x 32x32x16 MFMA N dimension)
-constexpr int kKindWave = 0;      // WorkItem::kind
+constexpr int kKindWave = 0;
 constexpr int kKindTile = 1;
+constexpr int kAppendTokensPerBlock = 8;  // tokens one block of the append kernel moves
 
-// One unit of attention work: a tile of query columns of one sequence against a key range.
-// A "column" is one (query row, query head inside a KV group) pair: col = row*G + head_in_group.
-// The same item runs once per KV head (the KV head is taken from the block index).
-struct WorkItem {
+// One tile of query columns of one sequence.  A "column" is one (query row, query head inside
+// a KV group) pair: col = row*G + head_in_group.  Its key range 0..n_keys-1 is cut into
+// n_splits pieces of keys_per_split keys (a multiple of 32; the last piece is shorter); every
+// piece is one work unit, run once per KV head.  The descriptor carries the sequence's lengths
+// so that a unit needs no further lookups.
+struct TileDesc {
     int32_t seq;
     int32_t col_begin;
     int32_t n_cols;
-    int32_t key_begin;   // multiple of kTileKeys
-    int32_t key_end;     // exclusive
-    int32_t part_row;    // first partial row, or -1: normalise and write `out` directly
     int32_t kind;
-    int32_t reserved;
-};
-static_assert(sizeof(WorkItem) == 32, "WorkItem is copied to the device as raw bytes");
-static_assert(sizeof(WorkItem) == sizeof(sarathi_work_item), "debug view must mirror WorkItem");
-
-// Merge of the splits of one tile: partial rows part_row + split*n_cols + col.
-struct ReduceItem {
-    int32_t seq;
-    int32_t col_begin;
-    int32_t n_cols;
-    int32_t part_row;
+    int32_t n_keys;
+    int32_t keys_per_split;
     int32_t n_splits;
-    int32_t reserved[3];
+    int32_t part_row0;    // first partial row of split 0 (split i uses part_row0 + i*n_cols ..), -1 if n_splits == 1
+    int32_t counter_idx;  // arrival counter of the tile (per KV head: counter_idx*Hkv + kv_head), -1 if n_splits == 1
+    int32_t q_start;
+    int32_t q_len;
+    int32_t ctx_len;
 };
-static_assert(sizeof(ReduceItem) == 32, "ReduceItem is copied to the device as raw bytes");
+static_assert(sizeof(TileDesc) == 48, "TileDesc is copied to the device as raw bytes");
+
+// A work unit = (tile index, split index) packed into 32 bits.
+constexpr int kUnitTileBits = 22;
+inline uint32_t pack_unit(uint32_t tile, uint32_t split) { return (split << kUnitTileBits) | tile; }
 
 struct Plan {
-    std::vector<WorkItem> items;          // chunk tiles first (num_tile_items of them), then wave tiles
-    int32_t num_tile_items = 0;
-    std::vector<ReduceItem> reduce_items;
+    std::vector<TileDesc> tiles;
+    std::vector<uint32_t> units;      // chunk-tile units first (num_tile_units), then wave-tile units; longest first in each group
+    int32_t num_tile_units = 0;
+    int32_t num_split_tiles = 0;      // tiles with n_splits > 1 (= arrival counters in use)
     int32_t num_part_rows = 0;
     int32_t split_keys = 0;
     int32_t tile_split_keys = 0;
@@ -56,23 +56,25 @@ struct Plan {
 
 // Byte offsets of the regions inside the caller's workspace (all 256-byte aligned).
 struct WorkspaceLayout {
-    size_t seq_meta;      // int32 [3][max_seqs]: q_start, q_len, ctx_len
-    size_t items;         // WorkItem [max_items]
-    size_t reduce_items;  // ReduceItem [max_reduce_items]
+    size_t meta;          // per-call metadata, packed: sequence arrays + hints (append) or tile descriptors + units (attention)
+    size_t meta_bytes;
+    size_t counters;      // int32 [max_split_tiles][Hkv] arrival counters, zero between calls
     size_t part_ml;       // float [max_part_rows][Hkv][2]
     size_t part_o;        // float [max_part_rows][Hkv][head_dim]
     size_t total;
-    int32_t max_items;
-    int32_t max_reduce_items;
+    int32_t max_tiles;
+    int32_t max_units;
+    int32_t max_split_tiles;
     int32_t max_part_rows;
 };
 
 struct Options {
-    int64_t split_keys = 0;      // 0 = automatic
-    int64_t target_items = 1536; // automatic choice aims for about this many wave items per KV head
-    int64_t tile_split_keys = 0;  // the same two knobs for the 128-column chunk tiles
+    int64_t split_keys = 0;         // 0 = automatic
+    int64_t target_items = 1536;    // automatic choice aims for about this many wave units per KV head
+    int64_t tile_split_keys = 0;    // the same two knobs for the 128-column chunk tiles
     int64_t tile_target_items = 96;
-    int64_t tile_min_cols = 64;   // sequences with fewer columns (q_len*G) use wave tiles only
+    int64_t tile_min_cols = 64;     // sequences with fewer columns (q_len*G) use wave tiles only
+    int64_t interleave = 1;         // alternate chunk-tile blocks and wave-tile blocks in the grid
 };
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg);
@@ -84,27 +86,38 @@ sarathi_status validate_batch(const sarathi_config &cfg, const int32_t *q_start,
 
 // Work decomposition for sarathi_hybrid_attention.
 void plan_attention(const sarathi_config &cfg, const Options &opt, const WorkspaceLayout &ws,
-                    const int32_t *q_len, const int32_t *ctx_len, int32_t num_seqs, Plan &plan);
+                    const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len, int32_t num_seqs,
+                    Plan &plan);
 
 // ---- device launchers (attn_kernels.hip); each returns a hipError_t cast to int ----
-struct DeviceBatch {
+struct AppendMeta {
     const int32_t *q_start;      // dev [S]
     const int32_t *q_len;        // dev [S]
     const int32_t *ctx_len;      // dev [S]
+    const int32_t *block_hint;   // dev [ceil(T / kAppendTokensPerBlock)]: sequence owning the block's first token
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
     int32_t num_seqs;
     int32_t num_tokens;
 };
 
-int launch_kv_append(const sarathi_config &cfg, const DeviceBatch &b, const void *k_new, const void *v_new,
+int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void *k_new, const void *v_new,
                      void *k_cache, void *v_cache, int64_t num_pages, void *stream);
 
-int launch_attention(const sarathi_config &cfg, const DeviceBatch &b, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, const WorkItem *items,
-                     int32_t num_tile_items, int32_t num_items, float *part_ml, float *part_o, void *stream);
+struct AttnMeta {
+    const TileDesc *tiles;       // dev
+    const uint32_t *units;       // dev
+    int32_t num_tile_units;
+    int32_t num_units;
+    int32_t interleave;
+    const int32_t *block_table;  // dev [S][max_blocks]
+    int32_t max_blocks;
+    int32_t *counters;           // dev
+    float *part_ml;              // dev
+    float *part_o;               // dev
+};
 
-int launch_reduce(const sarathi_config &cfg, const DeviceBatch &b, const ReduceItem *items, int32_t num_items,
-                  const float *part_ml, const float *part_o, void *out, void *stream);
+int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, void *stream);
 
 }  // namespace sarathi

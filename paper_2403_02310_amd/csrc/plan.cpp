@@ -8,8 +8,9 @@
 // 0 .. position of its last row.  Long key ranges are cut into splits of about `split_keys`
 // keys so that (a) a decode with a long context (paper section 3.3: decode cost grows with
 // the accumulated context and differs across requests) does not become the tail of the
-// launch and (b) there are enough items to fill 256 compute units.  Splits are merged by a
-// second kernel in a fixed order.
+// launch and (b) there are enough units to fill 256 compute units.  Chunks with at least
+// tile_min_cols columns use 128-column tiles instead (K/V staged once per tile in LDS).  The
+// splits of a tile are merged, in index order, by whichever of them finishes last.
 #include <algorithm>
 #include <cstdio>
 
@@ -20,7 +21,7 @@ namespace sarathi {
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-constexpr int32_t kMaxSplitItems = 8192;
+constexpr int32_t kMaxSplitUnits = 8192;
 constexpr int32_t kMaxPartRows = 32768;
 constexpr int32_t kMinSplitKeys = 256;
 constexpr int32_t kMinTileSplitKeys = 1024;
@@ -31,15 +32,20 @@ WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
     // wave tiles only exist for sequences below tile_min_cols columns; bounding every sequence by
     // 16-column tiles covers both kinds
     const int64_t max_tiles = ceil_div((int64_t)cfg.max_tokens * G, kWaveCols) + cfg.max_seqs;
-    w.max_items = (int32_t)std::min<int64_t>(max_tiles + kMaxSplitItems, INT32_MAX / 64);
-    w.max_reduce_items = (int32_t)std::min<int64_t>(max_tiles, INT32_MAX / 64);
+    w.max_tiles = (int32_t)std::min<int64_t>(max_tiles, INT32_MAX / 64);
+    w.max_units = (int32_t)std::min<int64_t>(max_tiles + kMaxSplitUnits, INT32_MAX / 64);
+    w.max_split_tiles = (int32_t)std::min<int64_t>(max_tiles, kMaxSplitUnits / 2);
     w.max_part_rows = kMaxPartRows;
+    const size_t attn_meta = sizeof(TileDesc) * (size_t)w.max_tiles + sizeof(uint32_t) * (size_t)w.max_units + 64;
+    const size_t append_meta = sizeof(int32_t) * (3 * (size_t)cfg.max_seqs +
+                                                  (size_t)ceil_div(cfg.max_tokens, kAppendTokensPerBlock)) + 64;
     size_t off = 0;
-    w.seq_meta = off;      off = align_up(off + sizeof(int32_t) * 3 * (size_t)cfg.max_seqs, 256);
-    w.items = off;         off = align_up(off + sizeof(WorkItem) * (size_t)w.max_items, 256);
-    w.reduce_items = off;  off = align_up(off + sizeof(ReduceItem) * (size_t)w.max_reduce_items, 256);
-    w.part_ml = off;       off = align_up(off + sizeof(float) * 2 * (size_t)w.max_part_rows * cfg.num_kv_heads, 256);
-    w.part_o = off;        off = align_up(off + sizeof(float) * (size_t)w.max_part_rows * cfg.num_kv_heads * cfg.head_dim, 256);
+    w.meta = off;
+    w.meta_bytes = align_up(std::max(attn_meta, append_meta), 256);
+    off += w.meta_bytes;
+    w.counters = off;  off = align_up(off + sizeof(int32_t) * (size_t)w.max_split_tiles * cfg.num_kv_heads, 256);
+    w.part_ml = off;   off = align_up(off + sizeof(float) * 2 * (size_t)w.max_part_rows * cfg.num_kv_heads, 256);
+    w.part_o = off;    off = align_up(off + sizeof(float) * (size_t)w.max_part_rows * cfg.num_kv_heads * cfg.head_dim, 256);
     w.total = off;
     return w;
 }
@@ -82,113 +88,129 @@ sarathi_status validate_batch(const sarathi_config &cfg, const int32_t *q_start,
 
 namespace {
 
-struct Tile {
-    int32_t seq, col_begin, n_cols, n_keys;
-};
-
-inline int32_t steps_of(const WorkItem &w) { return (int32_t)ceil_div(w.key_end - w.key_begin, kTileKeys); }
-
-// Emits the items of one kind for `tiles`, splitting key ranges longer than ~1.5 * split_keys,
-// and appends them to `out` sorted longest first (counting sort on 32-key steps).
-void emit_items(const std::vector<Tile> &tiles, int64_t split_keys, int32_t kind, Plan &plan,
-                std::vector<WorkItem> &scratch, std::vector<int32_t> &bucket) {
-    scratch.clear();
-    int32_t max_steps = 0;
-    for (const Tile &t : tiles) {
-        int32_t ns = (t.n_keys <= split_keys + split_keys / 2) ? 1 : (int32_t)ceil_div(t.n_keys, split_keys);
-        const int32_t per = (int32_t)(ceil_div(ceil_div(t.n_keys, ns), kTileKeys) * kTileKeys);
-        ns = (int32_t)ceil_div(t.n_keys, per);
-        int32_t part_row = -1;
-        if (ns > 1) {
-            part_row = plan.num_part_rows;
-            plan.num_part_rows += ns * t.n_cols;
-            plan.reduce_items.push_back({t.seq, t.col_begin, t.n_cols, part_row, ns, {0, 0, 0}});
-        }
-        for (int32_t i = 0; i < ns; ++i) {
-            WorkItem w{};
-            w.seq = t.seq;
-            w.col_begin = t.col_begin;
-            w.n_cols = t.n_cols;
-            w.key_begin = i * per;
-            w.key_end = std::min(t.n_keys, (i + 1) * per);
-            w.part_row = ns > 1 ? part_row + i * t.n_cols : -1;
-            w.kind = kind;
-            scratch.push_back(w);
-            max_steps = std::max(max_steps, steps_of(w));
-        }
-    }
-    bucket.assign((size_t)max_steps + 2, 0);
-    for (const WorkItem &w : scratch) bucket[(size_t)(max_steps - steps_of(w)) + 1]++;
-    for (size_t i = 1; i < bucket.size(); ++i) bucket[i] += bucket[i - 1];
-    const size_t base = plan.items.size();
-    plan.items.resize(base + scratch.size());
-    for (const WorkItem &w : scratch) plan.items[base + (size_t)bucket[(size_t)(max_steps - steps_of(w))]++] = w;
+inline int32_t steps_of_split(const TileDesc &t, int32_t split) {
+    const int32_t b = split * t.keys_per_split;
+    const int32_t e = std::min(t.n_keys, b + t.keys_per_split);
+    return (int32_t)ceil_div(e - b, kTileKeys);
 }
 
-// Split items and partial rows a choice of split_keys would need.
-void count_splits(const std::vector<Tile> &tiles, int64_t split_keys, int64_t &n_split_items, int64_t &rows) {
-    for (const Tile &t : tiles) {
+// Chooses the split of every tile in [first, last) for `split_keys`, assigns partial rows and
+// counters, and appends the units sorted longest first (counting sort on 32-key steps).
+void emit_units(Plan &plan, size_t first, size_t last, int64_t split_keys, std::vector<uint32_t> &scratch,
+                std::vector<int32_t> &bucket) {
+    scratch.clear();
+    int32_t max_steps = 0;
+    for (size_t ti = first; ti < last; ++ti) {
+        TileDesc &t = plan.tiles[ti];
+        int32_t ns = (t.n_keys <= split_keys + split_keys / 2) ? 1 : (int32_t)ceil_div(t.n_keys, split_keys);
+        t.keys_per_split = (int32_t)(ceil_div(ceil_div(t.n_keys, ns), kTileKeys) * kTileKeys);
+        t.n_splits = (int32_t)ceil_div(t.n_keys, t.keys_per_split);
+        if (t.n_splits > 1) {
+            t.part_row0 = plan.num_part_rows;
+            plan.num_part_rows += t.n_splits * t.n_cols;
+            t.counter_idx = plan.num_split_tiles++;
+        } else {
+            t.part_row0 = -1;
+            t.counter_idx = -1;
+        }
+        for (int32_t i = 0; i < t.n_splits; ++i) {
+            scratch.push_back(pack_unit((uint32_t)ti, (uint32_t)i));
+            max_steps = std::max(max_steps, steps_of_split(t, i));
+        }
+    }
+    auto steps = [&](uint32_t u) {
+        return steps_of_split(plan.tiles[u & ((1u << kUnitTileBits) - 1)], (int32_t)(u >> kUnitTileBits));
+    };
+    bucket.assign((size_t)max_steps + 2, 0);
+    for (uint32_t u : scratch) bucket[(size_t)(max_steps - steps(u)) + 1]++;
+    for (size_t i = 1; i < bucket.size(); ++i) bucket[i] += bucket[i - 1];
+    const size_t base = plan.units.size();
+    plan.units.resize(base + scratch.size());
+    for (uint32_t u : scratch) plan.units[base + (size_t)bucket[(size_t)(max_steps - steps(u))]++] = u;
+}
+
+// Split units, partial rows and split tiles a choice of split_keys would need for tiles [first, last).
+void count_splits(const Plan &plan, size_t first, size_t last, int64_t split_keys, int64_t &n_split_units,
+                  int64_t &rows, int64_t &n_split_tiles) {
+    for (size_t ti = first; ti < last; ++ti) {
+        const TileDesc &t = plan.tiles[ti];
         if (t.n_keys <= split_keys + split_keys / 2) continue;
         const int64_t ns = ceil_div(t.n_keys, split_keys);
-        n_split_items += ns;
+        n_split_units += ns;
         rows += ns * t.n_cols;
+        n_split_tiles++;
     }
 }
 
 }  // namespace
 
 void plan_attention(const sarathi_config &cfg, const Options &opt, const WorkspaceLayout &ws,
-                    const int32_t *q_len, const int32_t *ctx_len, int32_t num_seqs, Plan &plan) {
-    plan.items.clear();
-    plan.reduce_items.clear();
+                    const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len, int32_t num_seqs,
+                    Plan &plan) {
+    plan.tiles.clear();
+    plan.units.clear();
     plan.num_part_rows = 0;
-    plan.num_tile_items = 0;
+    plan.num_tile_units = 0;
+    plan.num_split_tiles = 0;
     const int32_t G = cfg.num_q_heads / cfg.num_kv_heads;
 
-    static thread_local std::vector<Tile> wave_tiles, chunk_tiles;
-    static thread_local std::vector<WorkItem> scratch;
-    static thread_local std::vector<int32_t> bucket;
-    wave_tiles.clear();
-    chunk_tiles.clear();
-    int64_t wave_keys = 0, chunk_keys = 0;
-    for (int32_t s = 0; s < num_seqs; ++s) {
-        const int32_t prefix = ctx_len[s] - q_len[s];
-        const int64_t n_cols = (int64_t)q_len[s] * G;
-        const bool chunk = n_cols >= opt.tile_min_cols;   // prefill chunk: 128-column LDS-staged tiles
-        const int32_t width = chunk ? kTileCols : kWaveCols;
-        for (int64_t c0 = 0; c0 < n_cols; c0 += width) {
-            const int32_t nc = (int32_t)std::min<int64_t>(width, n_cols - c0);
-            const int32_t last_row = (int32_t)((c0 + nc - 1) / G);
-            const int32_t n_keys = prefix + last_row + 1;   // keys 0 .. position of the tile's last row
-            if (chunk) { chunk_tiles.push_back({s, (int32_t)c0, nc, n_keys}); chunk_keys += n_keys; }
-            else       { wave_tiles.push_back({s, (int32_t)c0, nc, n_keys});  wave_keys += n_keys; }
+    // Tiles: chunk tiles first, then wave tiles (two passes keep each kind contiguous).
+    int64_t keys_of_kind[2] = {0, 0};
+    size_t n_chunk_tiles = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int32_t kind = pass == 0 ? kKindTile : kKindWave;
+        for (int32_t s = 0; s < num_seqs; ++s) {
+            const int64_t n_cols = (int64_t)q_len[s] * G;
+            const bool chunk = n_cols >= opt.tile_min_cols;   // prefill chunk: 128-column LDS-staged tiles
+            if (chunk != (kind == kKindTile)) continue;
+            const int32_t prefix = ctx_len[s] - q_len[s];
+            const int32_t width = chunk ? kTileCols : kWaveCols;
+            for (int64_t c0 = 0; c0 < n_cols; c0 += width) {
+                TileDesc t{};
+                t.seq = s;
+                t.col_begin = (int32_t)c0;
+                t.n_cols = (int32_t)std::min<int64_t>(width, n_cols - c0);
+                t.kind = kind;
+                t.n_keys = prefix + (int32_t)((c0 + t.n_cols - 1) / G) + 1;  // keys 0 .. position of the tile's last row
+                t.q_start = q_start[s];
+                t.q_len = q_len[s];
+                t.ctx_len = ctx_len[s];
+                plan.tiles.push_back(t);
+                keys_of_kind[kind] += t.n_keys;
+            }
         }
+        if (pass == 0) n_chunk_tiles = plan.tiles.size();
     }
 
-    // Keys per split: the automatic choice aims at ~target items per KV head, never below a
-    // floor, and both are coarsened together until the partial buffers suffice.
+    // Keys per split: the automatic choice aims at ~target units per KV head, never below a
+    // floor, and both kinds are coarsened together until the partial buffers suffice.
     auto pick = [](int64_t forced, int64_t total, int64_t target, int64_t floor_keys) {
         int64_t k = forced > 0 ? forced : std::max<int64_t>(floor_keys, ceil_div(total, std::max<int64_t>(1, target)));
         return ceil_div(k, kTileKeys) * kTileKeys;
     };
-    int64_t wave_split = pick(opt.split_keys, wave_keys, opt.target_items, kMinSplitKeys);
-    int64_t tile_split = pick(opt.tile_split_keys, chunk_keys, opt.tile_target_items, kMinTileSplitKeys);
+    int64_t wave_split = pick(opt.split_keys, keys_of_kind[kKindWave], opt.target_items, kMinSplitKeys);
+    int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], opt.tile_target_items, kMinTileSplitKeys);
     for (;;) {
-        int64_t n_split_items = 0, rows = 0;
-        count_splits(wave_tiles, wave_split, n_split_items, rows);
-        count_splits(chunk_tiles, tile_split, n_split_items, rows);
-        if (n_split_items <= kMaxSplitItems && rows <= ws.max_part_rows &&
-            (int64_t)wave_tiles.size() + (int64_t)chunk_tiles.size() + n_split_items <= ws.max_items)
-            break;
+        int64_t n_split_units = 0, rows = 0, n_split_tiles = 0;
+        count_splits(plan, 0, n_chunk_tiles, tile_split, n_split_units, rows, n_split_tiles);
+        count_splits(plan, n_chunk_tiles, plan.tiles.size(), wave_split, n_split_units, rows, n_split_tiles);
+        const int64_t max_splits_per_tile = (1 << (32 - kUnitTileBits)) - 1;
+        bool fits = n_split_units <= kMaxSplitUnits && rows <= ws.max_part_rows && n_split_tiles <= ws.max_split_tiles &&
+                    (int64_t)plan.tiles.size() + n_split_units <= ws.max_units;
+        for (const TileDesc &t : plan.tiles)
+            if (ceil_div(t.n_keys, t.kind == kKindTile ? tile_split : wave_split) > max_splits_per_tile) { fits = false; break; }
+        if (fits) break;
         wave_split *= 2;
         tile_split *= 2;
     }
     plan.split_keys = (int32_t)std::min<int64_t>(wave_split, INT32_MAX);
     plan.tile_split_keys = (int32_t)std::min<int64_t>(tile_split, INT32_MAX);
 
-    emit_items(chunk_tiles, tile_split, kKindTile, plan, scratch, bucket);
-    plan.num_tile_items = (int32_t)plan.items.size();
-    emit_items(wave_tiles, wave_split, kKindWave, plan, scratch, bucket);
+    static thread_local std::vector<uint32_t> scratch;
+    static thread_local std::vector<int32_t> bucket;
+    emit_units(plan, 0, n_chunk_tiles, tile_split, scratch, bucket);
+    plan.num_tile_units = (int32_t)plan.units.size();
+    emit_units(plan, n_chunk_tiles, plan.tiles.size(), wave_split, scratch, bucket);
 }
 
 }  // namespace sarathi
