@@ -215,6 +215,7 @@ def main() -> int:
         attn_us = kt.attention_ms * 1e3 / kt.attention_launches
         result["kernel_us"] = {
             "attention": attn_us,
+            "merge": (kt.merge_ms * 1e3 / kt.merge_launches) if kt.merge_launches else 0.0,
             "kv_append": (kt.append_ms * 1e3 / kt.append_launches) if kt.append_launches else 0.0,
             "launches": int(kt.attention_launches)}
         mfma_bound = args.workload.endswith("_chunk") or args.workload.endswith("_chunks")

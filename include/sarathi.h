@@ -104,8 +104,8 @@ sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int6
  * between two reads).  sarathi_get_kernel_times waits for the recorded events, returns the
  * summed durations and launch counts since the last read, and resets them. */
 typedef struct {
-    double append_ms, attention_ms;
-    int64_t append_launches, attention_launches;
+    double append_ms, attention_ms, merge_ms;
+    int64_t append_launches, attention_launches, merge_launches;
 } sarathi_kernel_times;
 sarathi_status sarathi_get_kernel_times(sarathi_handle *handle, sarathi_kernel_times *out);
 
@@ -136,17 +136,15 @@ sarathi_status sarathi_kv_append(sarathi_handle *handle,
  *
  *   q              dev, bf16 [num_tokens, Hq, head_dim], batch order
  *   k_cache, v_cache, block_table, q_start, q_len, ctx_len, num_pages: as above (read only)
- *   sm_scale       multiplies every score before the softmax (callers use 1/sqrt(head_dim))
+ *   sm_scale       multiplies every score before the softmax; positive and finite (callers use 1/sqrt(head_dim))
  *   out            dev, bf16 [num_tokens, Hq, head_dim] (written; fp32 accumulation, one
  *                  round-to-nearest-even at the end)
  *
  * Prefill-chunk rows and decode rows run in the same launch; long key ranges are split
  * into independent pieces whose partial (max, sum, unnormalised output) triples are merged
- * in a fixed order by the piece that finishes last, so results are bitwise reproducible
- * run to run and do not depend on which physical pages hold the data.  The first call
- * with a given workspace clears a small counter region inside it with hipMemsetAsync (do
- * not make that first call inside a stream capture); later calls enqueue only one
- * host-to-device copy of the batch metadata and one kernel.
+ * in a fixed order by a second small kernel, so results are bitwise reproducible run to
+ * run and do not depend on which physical pages hold the data.  A call enqueues one
+ * host-to-device copy of the batch metadata and one or two kernels.
  */
 sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
                                         const void *q,
@@ -172,7 +170,7 @@ typedef struct {
 
 typedef struct {
     int32_t num_items;        /* work items (each runs once per KV head) */
-    int32_t num_reduce_items; /* tiles whose key range was split (their pieces are merged by the last to finish) */
+    int32_t num_reduce_items; /* tiles whose key range was split (their pieces are merged by the second kernel) */
     int32_t num_part_rows;    /* rows of partial results used */
     int32_t split_keys;       /* keys per split the planner settled on for wave tiles */
     int32_t num_tile_items;   /* the first num_tile_items items are chunk tiles */

@@ -56,8 +56,9 @@ class Batch(ctypes.Structure):
 
 
 class KernelTimes(ctypes.Structure):
-    _fields_ = [("append_ms", ctypes.c_double), ("attention_ms", ctypes.c_double),
-                ("append_launches", ctypes.c_int64), ("attention_launches", ctypes.c_int64)]
+    _fields_ = [("append_ms", ctypes.c_double), ("attention_ms", ctypes.c_double), ("merge_ms", ctypes.c_double),
+                ("append_launches", ctypes.c_int64), ("attention_launches", ctypes.c_int64),
+                ("merge_launches", ctypes.c_int64)]
 
 
 EXPORTED = ["sarathi_create", "sarathi_destroy", "sarathi_workspace_bytes", "sarathi_last_error",

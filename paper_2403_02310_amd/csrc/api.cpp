@@ -34,12 +34,10 @@ struct sarathi_handle {
     size_t staging_bytes = 0;
     int next_slot = 0;
     bool staging_ready = false;
-    // Workspace whose arrival counters this handle has zeroed (they stay zero between calls).
-    void *counters_ready_for = nullptr;
     // Optional per-kernel timing: event pairs recorded around each launch.
     bool time_kernels = false;
-    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[2];  // append, attention
-    size_t timing_used[2] = {0, 0};
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, merge
+    size_t timing_used[3] = {0, 0, 0};
 };
 
 namespace {
@@ -183,9 +181,9 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
 
 extern "C" sarathi_status sarathi_get_kernel_times(sarathi_handle *h, sarathi_kernel_times *out) {
     if (!h || !out) return SARATHI_EINVAL;
-    double ms[2] = {0, 0};
-    int64_t n[2] = {0, 0};
-    for (int kind = 0; kind < 2; ++kind) {
+    double ms[3] = {0, 0, 0};
+    int64_t n[3] = {0, 0, 0};
+    for (int kind = 0; kind < 3; ++kind) {
         for (size_t i = 0; i < h->timing_used[kind]; ++i) {
             auto &pr = h->timing_pool[kind][i];
             hipError_t e = hipEventSynchronize(pr.second);
@@ -198,8 +196,8 @@ extern "C" sarathi_status sarathi_get_kernel_times(sarathi_handle *h, sarathi_ke
         }
         h->timing_used[kind] = 0;
     }
-    out->append_ms = ms[0]; out->attention_ms = ms[1];
-    out->append_launches = n[0]; out->attention_launches = n[1];
+    out->append_ms = ms[0]; out->attention_ms = ms[1]; out->merge_ms = ms[2];
+    out->append_launches = n[0]; out->attention_launches = n[1]; out->merge_launches = n[2];
     return SARATHI_OK;
 }
 
@@ -253,20 +251,20 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     int slot;
     if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
 
-    // Metadata: q_start | q_len | ctx_len | per-block owner of the block's first token.
+    // Metadata: q_start | prefix | per-block owner of the block's first token.
     int32_t *host = static_cast<int32_t *>(h->staging[slot]);
     const size_t n = (size_t)num_seqs;
     std::memcpy(host, q_start, sizeof(int32_t) * n);
-    std::memcpy(host + n, q_len, sizeof(int32_t) * n);
-    std::memcpy(host + 2 * n, ctx_len, sizeof(int32_t) * n);
-    int32_t *hint = host + 3 * n;
-    const int32_t n_blocks = (num_tokens + kAppendTokensPerBlock - 1) / kAppendTokensPerBlock;
-    for (int32_t b = 0, s = 0; b < n_blocks; ++b) {
-        const int32_t t = b * kAppendTokensPerBlock;
-        while (s + 1 < num_seqs && q_start[s + 1] <= t) ++s;
-        hint[b] = s;
+    for (size_t i = 0; i < n; ++i) host[n + i] = ctx_len[i] - q_len[i];
+    int32_t *hint = host + 2 * n;
+    const int64_t n_blocks = append_blocks(h->cfg, num_tokens);
+    const int64_t threads_per_token = (int64_t)h->cfg.num_kv_heads * (h->cfg.head_dim / 8);
+    for (int64_t b = 0, sq = 0; b < n_blocks; ++b) {
+        const int64_t t = b * 256 / threads_per_token;
+        while (sq + 1 < num_seqs && q_start[sq + 1] <= t) ++sq;
+        hint[b] = (int32_t)sq;
     }
-    const size_t used = sizeof(int32_t) * (3 * n + (size_t)n_blocks);
+    const size_t used = sizeof(int32_t) * (2 * n + (size_t)n_blocks);
     if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
 
     char *dev = static_cast<char *>(workspace) + h->ws.meta;
@@ -279,9 +277,8 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
 
     AppendMeta m;
     m.q_start = reinterpret_cast<const int32_t *>(dev);
-    m.q_len = m.q_start + n;
-    m.ctx_len = m.q_len + n;
-    m.block_hint = m.ctx_len + n;
+    m.prefix = m.q_start + n;
+    m.block_hint = m.prefix + n;
     m.block_table = block_table;
     m.max_blocks = h->cfg.max_blocks_per_seq;
     m.num_seqs = num_seqs;
@@ -304,7 +301,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     if (st != SARATHI_OK) return st;
     if (num_seqs == 0) return SARATHI_OK;
     if (!q || !k_cache || !v_cache || !block_table || !out) return fail(h, SARATHI_EINVAL, "null tensor pointer");
-    if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale is not finite");
+    if (!(sm_scale > 0.0f) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale must be positive and finite");
     if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
     plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
     const Plan &pl = h->plan;
@@ -315,22 +312,17 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     char *ws = static_cast<char *>(workspace);
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (h->counters_ready_for != workspace) {
-        // First use of this workspace: the arrival counters must start at zero; every launch
-        // leaves them at zero again.
-        e = hipMemsetAsync(ws + h->ws.counters, 0, sizeof(int32_t) * (size_t)h->ws.max_split_tiles * h->cfg.num_kv_heads, s);
-        if (e != hipSuccess) return hip_fail(h, "hipMemsetAsync(counters)", e);
-        h->counters_ready_for = workspace;
-    }
 
-    // Metadata packed back to back: tile descriptors, then work units; one copy.
+    // Metadata packed back to back: tile descriptors, work units, merge units; one copy.
     char *host = static_cast<char *>(h->staging[slot]);
     const size_t tiles_bytes = sizeof(TileDesc) * pl.tiles.size();
     const size_t units_off = align_up(tiles_bytes, 16);
-    const size_t used = units_off + sizeof(uint32_t) * pl.units.size();
+    const size_t reduce_off = units_off + sizeof(uint32_t) * pl.units.size();
+    const size_t used = reduce_off + sizeof(uint32_t) * pl.reduce_units.size();
     if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
     std::memcpy(host, pl.tiles.data(), tiles_bytes);
     std::memcpy(host + units_off, pl.units.data(), sizeof(uint32_t) * pl.units.size());
+    std::memcpy(host + reduce_off, pl.reduce_units.data(), sizeof(uint32_t) * pl.reduce_units.size());
     char *dev = ws + h->ws.meta;
     e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
@@ -346,12 +338,19 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.interleave = (int32_t)h->opt.interleave;
     m.block_table = block_table;
     m.max_blocks = h->cfg.max_blocks_per_seq;
-    m.counters = reinterpret_cast<int32_t *>(ws + h->ws.counters);
+    m.reduce_units = reinterpret_cast<const uint32_t *>(dev + reduce_off);
+    m.num_reduce_units = (int32_t)pl.reduce_units.size();
     m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     const int t1 = timing_begin(h, 1, s);
     e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, stream);
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);
+    if (m.num_reduce_units > 0) {
+        const int t2 = timing_begin(h, 2, s);
+        e = (hipError_t)launch_reduce(h->cfg, m, out, stream);
+        timing_end(h, 2, t2, s);
+        if (e != hipSuccess) return hip_fail(h, "launch split-KV merge", e);
+    }
     return SARATHI_OK;
 }

@@ -37,10 +37,11 @@
 // the accumulator rescale from almost every tile.
 //
 // Split-KV.  A tile whose key range was cut into pieces has every piece write its partial
-// (reference maximum, sum, unnormalised output) triple and bump the tile's arrival counter;
-// the piece that arrives last re-reads all partials in index order, merges them and writes the
-// final rows.  The merge order is fixed, so the result is bitwise reproducible no matter which
-// piece finishes last.  Counters are left at zero for the next call.
+// (reference maximum, sum, unnormalised output) triple; a second, small kernel merges the
+// pieces of each tile in index order, so the result is bitwise reproducible.  (Merging inside
+// the attention kernel by the last piece to finish was tried and dropped: on this multi-die
+// part the device-scope release/acquire fences it needs write back and invalidate whole L2s
+// and made the kernel several times slower.)
 //
 // Masking is by select: keys beyond a column's position (causal mask inside a chunk, section
 // 4.1 of the paper) or beyond the item's key range get score -inf; V of slots at or beyond
@@ -68,7 +69,6 @@ struct AttnParams {
     const int32_t *block_table;
     const TileDesc *tiles;
     const uint32_t *units;
-    int32_t *counters;
     float *part_ml;
     float *part_o;
     int64_t num_pages;
@@ -280,7 +280,7 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
         }
         return;
     }
-    // Split tile: publish this piece, then the last piece to arrive merges all of them.
+    // Split tile: publish this piece's (reference maximum, sum, unnormalised output).
     if (col_valid) {
         const int64_t prow = ((int64_t)(ur.part_row + n) * p.num_kv_heads + kvh);
         float *po = p.part_o + prow * D + g * 4;
@@ -291,61 +291,108 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
             p.part_ml[prow * 2 + 1] = l;
         }
     }
-    int32_t *counter = p.counters + (int64_t)it.counter_idx * p.num_kv_heads + kvh;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the whole wave's partial stores before the arrival
-    int arrived = 0;
-    if (lane == 0) arrived = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    arrived = __shfl(arrived, 0);
-    if (arrived != it.n_splits - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other pieces' stores are visible from here on
-    if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
-    if (!col_valid) return;
-    float m_max = kNegSentinel;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + n) * p.num_kv_heads + kvh);
-        m_max = fmaxf(m_max, p.part_ml[prow * 2]);
-    }
-    f32x4 acc[D / 16];
-#pragma unroll
-    for (int c = 0; c < D / 16; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float lsum = 0.f;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + n) * p.num_kv_heads + kvh);
-        const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
-        lsum += w * p.part_ml[prow * 2 + 1];
-        const float *po = p.part_o + prow * D + g * 4;
-#pragma unroll
-        for (int c = 0; c < D / 16; ++c) acc[c] += *reinterpret_cast<const f32x4 *>(po + c * 16) * w;
-    }
-    const float inv = 1.0f / lsum;
-#pragma unroll
-    for (int c = 0; c < D / 16; ++c) {
-        const bf16x4 o4 = __builtin_convertvector(acc[c] * inv, bf16x4);
-        *reinterpret_cast<u32x2 *>(op + c * 16) = __builtin_bit_cast(u32x2, o4);
-    }
 }
 
 // ---------------------------------------------------------------------------------------
 // Chunk-tile path: 4 waves x 32 columns, K/V tiles of 32 keys staged in LDS.
 // ---------------------------------------------------------------------------------------
+constexpr int kRing = 4;  // LDS tile buffers of the chunk-tile path
+
 template <int D>
 struct ChunkSmem {
-    static constexpr int kKElems = kTileKeys * D;          // K tile: 32 rows of D channels
+    static constexpr int kKStride = D + 8;                 // K rows padded by 16 bytes: conflict-free b128 reads
+    static constexpr int kKElems = kTileKeys * kKStride;   // K tile: 32 rows
     static constexpr int kVElems = 2 * D * kPageSize;      // V tile: two pages of D x 16
     static constexpr int kBufElems = kKElems + kVElems;
-    static constexpr int kTotalElems = 2 * kBufElems;      // double buffered
+    static constexpr int kTotalElems = kRing * kBufElems;  // ring of tiles i-1 .. i+2
 };
 
-// LDS element offset of 16-byte chunk `c` of K row `r` (r = 16*page + slot).
-template <int D>
-__device__ __forceinline__ int k_lds_off(int r, int c) {
-    constexpr int CPR = D / 8;  // chunks per row
-    return (r * CPR + (c ^ (r & (CPR - 1)))) * 8;
-}
-// LDS element offset of the 8-slot half `hh` of V^T row `d` of page `u`.
+// LDS element offset of the 8-slot half `hh` of V^T row `d` of page `u`: the two halves of a
+// row are swapped on every other group of eight channels (conflict-free writes and reads).
 template <int D>
 __device__ __forceinline__ int v_lds_off(int u, int d, int hh) {
     return ((u * D + d) * 2 + (hh ^ ((d >> 3) & 1))) * 8;
+}
+
+__device__ __forceinline__ bf16x8 lds_bf16x8(const uint16_t *p) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
+}
+
+// State a wave carries from one tile to the next in the software-pipelined chunk loop.
+template <int D>
+struct ChunkState {
+    f32x16 oacc[D / 32];  // O^T accumulators: channel 32c + 8*(r/4) + 4h + r%4, column n
+    f32x16 s_cur;         // raw scores of the tile whose softmax is due (already masked)
+    bf16x8 p_prev[2];     // bf16 softmax weights of the previous tile (B operands of its output MFMAs)
+    float tmax;           // scaled maximum of s_cur over the column
+    float m_ref;          // softmax reference, scaled base-2 units
+    float l_run;          // this lane's share of the running sum
+};
+
+// One pipelined step.  Independent work of three tiles shares one basic block so that the
+// matrix pipe and the vector ALU run side by side inside a single wavefront:
+//   MFMA:  O^T += V^T(t-1) P^T(t-1)      (HAS_PREV)        S^T(t+1) = K(t+1) Q^T    (HAS_NEXT)
+//   VALU:  P(t) = 2^(S(t)*scale - m_ref), row sums, bf16 packing; mask and maximum of S(t+1)
+template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT>
+__device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qreg)[D / 16], const uint16_t *v_prev,
+                                           const uint16_t *k_next, float scale, int next_key0, int pos_eff) {
+    constexpr int NS = D / 16;
+    constexpr int NB = D / 32;
+    f32x16 s_next;
+    if (HAS_NEXT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_bf16x8(k_next + s * 16), qreg[s], s_next, 0, 0, 0);
+    }
+    if (HAS_PREV) {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            const bf16x8 v0 = lds_bf16x8(v_prev + (c * 32) * 16);
+            const bf16x8 v1 = lds_bf16x8(v_prev + (D + c * 32) * 16);
+            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, st.p_prev[0], st.oacc[c], 0, 0, 0);
+            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, st.p_prev[1], st.oacc[c], 0, 0, 0);
+        }
+    }
+    // softmax weights of the current tile against the (already sufficient) reference
+    f32x8 p0, p1;
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        p0[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s_cur[j], scale, -st.m_ref));
+        p1[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s_cur[8 + j], scale, -st.m_ref));
+        psum += p0[j] + p1[j];
+    }
+    st.l_run += psum;
+    st.p_prev[0] = __builtin_convertvector(p0, bf16x8);
+    st.p_prev[1] = __builtin_convertvector(p1, bf16x8);
+    if (HAS_NEXT) {
+        // register r of lane (h, n): key next_key0 + 16*(r/8) + r%8 , column n
+        if (MASK_NEXT) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                s_next[r] = (next_key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? s_next[r] : -INFINITY;
+        }
+        float smax = s_next[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) smax = fmaxf(smax, s_next[r]);
+        smax = fmaxf(smax, __shfl_xor(smax, 32));
+        st.tmax = smax * scale;  // scale > 0
+        st.s_cur = s_next;
+    }
+    // Issue order: every MFMA is followed by one LDS operand read and a few vector-ALU
+    // instructions, which execute while the matrix pipe works on that MFMA.
+    constexpr int kMfma = (HAS_PREV ? 2 * NB : 0) + (HAS_NEXT ? NS : 0);
+    if (kMfma > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // two operand reads ahead
+#pragma unroll
+        for (int i = 0; i < kMfma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // VALU
+        }
+    }
 }
 
 template <int D>
@@ -355,10 +402,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     constexpr int NB = D / 32;         // 32-channel blocks of the output
     constexpr int PER_THREAD = D / 64; // 16-byte chunks each thread stages per K (and per V) tile
     constexpr int PAGE_CHUNKS = 2 * D; // 16-byte chunks of one page of one KV head
+    constexpr int CPR = D / 8;         // 16-byte chunks per K row
     using SM = ChunkSmem<D>;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; tell the compiler
     const int n = lane & 31;
     const int h = lane >> 5;
     const int seq = it.seq;
@@ -391,8 +439,18 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     const int64_t head_off = (int64_t)kvh * kPageSize * D;
     const int64_t last_page_id = p.num_pages - 1;
 
-    // Staging: chunk index idx = tid + 256*j of the tile; page u = idx / PAGE_CHUNKS.
+    // Staging: chunk index idx = tid + 256*j of the tile; page u = idx / PAGE_CHUNKS.  The LDS
+    // destinations do not depend on the tile, so they are computed once.
     u32x4 kst[PER_THREAD], vst[PER_THREAD];
+    int st_k_off[PER_THREAD], st_v_off[PER_THREAD];
+#pragma unroll
+    for (int j = 0; j < PER_THREAD; ++j) {
+        const int idx = tid + 256 * j;
+        const int u = idx / PAGE_CHUNKS;
+        const int i = idx % PAGE_CHUNKS;
+        st_k_off[j] = (u * kPageSize + i / CPR) * SM::kKStride + (i % CPR) * 8;  // slot i/CPR, chunk i%CPR
+        st_v_off[j] = SM::kKElems + v_lds_off<D>(u, i >> 1, i & 1);              // channel i/2, slots 8*(i%2)..
+    }
     auto issue_loads = [&](int tile) {
 #pragma unroll
         for (int j = 0; j < PER_THREAD; ++j) {
@@ -407,103 +465,115 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         }
     };
     auto commit = [&](int tile, int buf) {
-        uint16_t *kb = smem + buf * SM::kBufElems;
-        uint16_t *vb = kb + SM::kKElems;
+        uint16_t *bb = smem + buf * SM::kBufElems;
         const bool tail = tile * kTileKeys + kTileKeys > ctx;  // tile holds slots at or beyond ctx_len
 #pragma unroll
         for (int j = 0; j < PER_THREAD; ++j) {
-            const int idx = tid + 256 * j;
-            const int u = idx / PAGE_CHUNKS;
-            const int i = idx % PAGE_CHUNKS;
-            // K: chunk i of the page = slot i/CPR, chunk i%CPR
-            *reinterpret_cast<u32x4 *>(kb + k_lds_off<D>(u * kPageSize + i / (D / 8), i % (D / 8))) = kst[j];
-            // V^T: chunk i of the page = channel i/2, slots 8*(i%2) ..
+            *reinterpret_cast<u32x4 *>(bb + st_k_off[j]) = kst[j];
             u32x4 v = vst[j];
             if (tail) {
-                const int key0 = tile * kTileKeys + u * kPageSize + (i & 1) * 8;
+                const int idx = tid + 256 * j;
+                const int key0 = tile * kTileKeys + (idx / PAGE_CHUNKS) * kPageSize + (idx & 1) * 8;
 #pragma unroll
                 for (int w = 0; w < 4; ++w)
                     v[w] &= ((key0 + 2 * w < ctx) ? 0x0000FFFFu : 0u) | ((key0 + 2 * w + 1 < ctx) ? 0xFFFF0000u : 0u);
             }
-            *reinterpret_cast<u32x4 *>(vb + v_lds_off<D>(u, i >> 1, i & 1)) = v;
+            *reinterpret_cast<u32x4 *>(bb + st_v_off[j]) = v;
         }
     };
 
-    f32x16 oacc[NB];
+    ChunkState<D> st;
 #pragma unroll
     for (int c = 0; c < NB; ++c)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
-    float m_ref = kNegSentinel;
-    float l_run = 0.f;
+        for (int r = 0; r < 16; ++r) st.oacc[c][r] = 0.f;
+    st.m_ref = kNegSentinel;
+    st.l_run = 0.f;
 
     // MFMA row n of the score tile is key  16u + 8h' + 4a + b  for n = 16u + 8a + 4h' + b.
     const int k_row = (n & 16) | ((n & 4) << 1) | ((n & 8) >> 1) | (n & 3);
+    const int k_rd = k_row * SM::kKStride + h * 8;          // + 16*s elements for contraction step s
+    const int v_rd = SM::kKElems + v_lds_off<D>(0, n, h);   // + (u*D + 32c)*16 elements for page u, channel block c
+    const float scale = p.scale_log2;
 
     const int tile_begin = ur.key_begin / kTileKeys;
     const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
+    auto needs_mask = [&](int tile) { return tile * kTileKeys + (kTileKeys - 1) > min_pos_eff; };  // wave-uniform
+
+    // Prologue: tiles 0 and 1 of the range go to LDS, tile 2 into the staging registers, and
+    // the scores of tile 0 are formed (as the "next" tile of an otherwise empty step).
     issue_loads(tile_begin);
     commit(tile_begin, 0);
+    if (tile_begin + 1 < tile_end) {
+        issue_loads(tile_begin + 1);
+        commit(tile_begin + 1, 1);
+    }
+    if (tile_begin + 2 < tile_end) issue_loads(tile_begin + 2);
     __syncthreads();
-    for (int tile = tile_begin; tile < tile_end; ++tile) {
-        const int buf = (tile - tile_begin) & 1;
-        const bool more = tile + 1 < tile_end;
-        if (more) issue_loads(tile + 1);
-        const uint16_t *kb = smem + buf * SM::kBufElems;
-        const uint16_t *vb = kb + SM::kKElems;
+    {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.s_cur[r] = -INFINITY;  // "current" tile of the empty step: weights 0
+        st.p_prev[0] = st.p_prev[1] = bf16x8{};
+        const uint16_t *k0 = smem + k_rd;
+        const int key0 = tile_begin * kTileKeys + h * 8;
+        if (needs_mask(tile_begin))
+            chunk_step<D, false, true, true>(st, qreg, nullptr, k0, scale, key0, pos_eff);
+        else
+            chunk_step<D, false, true, false>(st, qreg, nullptr, k0, scale, key0, pos_eff);
+        st.l_run = 0.f;  // the empty step contributed exp2(-inf) = 0 terms only
+    }
 
-        // S^T = K Q^T
-        f32x16 sacc;
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int rel = tile - tile_begin;
+        // staging: tile+2 (loaded during the previous step) enters the ring; tile+3 starts loading
+        if (tile + 2 < tile_end) commit(tile + 2, (rel + 2) & (kRing - 1));
+        if (tile + 3 < tile_end) issue_loads(tile + 3);
+        // raise the softmax reference if this tile exceeds it by more than the slack (rare)
+        if (__any(st.tmax > st.m_ref + kRescaleSlack)) {
+            const float m_new = fmaxf(st.m_ref, st.tmax);
+            const float alpha = __builtin_amdgcn_exp2f(st.m_ref - m_new);
+            st.l_run *= alpha;
+            st.m_ref = m_new;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kb + k_lds_off<D>(k_row, s * 2 + h)));
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], sacc, 0, 0, 0);
+            for (int c = 0; c < NB; ++c) st.oacc[c] *= alpha;
         }
-        // register r of lane (h, n): key  tile*32 + 16*(r/8) + 8h + r%8 , column n
-        const int key0 = tile * kTileKeys + h * 8;
-        float t[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t[r] = sacc[r] * p.scale_log2;
-        if (tile * kTileKeys + (kTileKeys - 1) > min_pos_eff) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) t[r] = (key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? t[r] : -INFINITY;
+        const uint16_t *v_prev = smem + ((rel - 1) & (kRing - 1)) * SM::kBufElems + v_rd;
+        const uint16_t *k_next = smem + ((rel + 1) & (kRing - 1)) * SM::kBufElems + k_rd;
+        const int next_key0 = (tile + 1) * kTileKeys + h * 8;
+        const bool has_prev = tile > tile_begin;
+        const bool has_next = tile + 1 < tile_end;
+        if (has_prev && has_next) {
+            if (needs_mask(tile + 1))
+                chunk_step<D, true, true, true>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
+            else
+                chunk_step<D, true, true, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
+        } else if (has_next) {
+            if (needs_mask(tile + 1))
+                chunk_step<D, false, true, true>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
+            else
+                chunk_step<D, false, true, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
+        } else if (has_prev) {
+            chunk_step<D, true, false, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
+        } else {
+            chunk_step<D, false, false, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
         }
-        float tmax = t[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, t[r]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        if (__any(tmax > m_ref + kRescaleSlack)) {
-            const float m_new = fmaxf(m_ref, tmax);
-            const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-            l_run *= alpha;
-            m_ref = m_new;
-#pragma unroll
-            for (int c = 0; c < NB; ++c) oacc[c] *= alpha;
-        }
-        f32x8 p0, p1;
-        float psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            p0[j] = __builtin_amdgcn_exp2f(t[j] - m_ref);
-            p1[j] = __builtin_amdgcn_exp2f(t[8 + j] - m_ref);
-            psum += p0[j] + p1[j];
-        }
-        l_run += psum;
-        const bf16x8 pT0 = __builtin_convertvector(p0, bf16x8);
-        const bf16x8 pT1 = __builtin_convertvector(p1, bf16x8);
-        // O^T += V^T P^T
-#pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            const bf16x8 a0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vb + v_lds_off<D>(0, c * 32 + n, h)));
-            const bf16x8 a1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vb + v_lds_off<D>(1, c * 32 + n, h)));
-            oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pT0, oacc[c], 0, 0, 0);
-            oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pT1, oacc[c], 0, 0, 0);
-        }
-        if (more) commit(tile + 1, buf ^ 1);
         __syncthreads();
     }
+    // Epilogue: the output MFMAs of the last tile.
+    {
+        const int rel = tile_end - 1 - tile_begin;
+        const uint16_t *v_last = smem + (rel & (kRing - 1)) * SM::kBufElems + v_rd;
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            const bf16x8 v0 = lds_bf16x8(v_last + (c * 32) * 16);
+            const bf16x8 v1 = lds_bf16x8(v_last + (D + c * 32) * 16);
+            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, st.p_prev[0], st.oacc[c], 0, 0, 0);
+            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, st.p_prev[1], st.oacc[c], 0, 0, 0);
+        }
+    }
+    f32x16 (&oacc)[NB] = st.oacc;
+    const float l_run = st.l_run;
+    const float m_ref = st.m_ref;
 
     const float l = l_run + __shfl_xor(l_run, 32);
     // accumulator register r of block c: channel 32c + 8*(r/4) + 4h + r%4
@@ -521,7 +591,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
             }
         return;
     }
-    // Split tile: publish this piece, then the last piece to arrive merges all of them.
+    // Split tile: publish this piece's (reference maximum, sum, unnormalised output).
     if (col_valid) {
         const int64_t prow = ((int64_t)(ur.part_row + wcol) * p.num_kv_heads + kvh);
         float *po = p.part_o + prow * D + h * 4;
@@ -537,86 +607,83 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
             p.part_ml[prow * 2 + 1] = l;
         }
     }
-    int32_t *counter = p.counters + (int64_t)it.counter_idx * p.num_kv_heads + kvh;
-    int *flag = reinterpret_cast<int *>(smem);  // the tile loop has drained: LDS is free
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __syncthreads();
-    if (tid == 0) *flag = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    const int arrived = *flag;
-    if (arrived != it.n_splits - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
-    if (!col_valid) return;
-    float m_max = kNegSentinel;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + wcol) * p.num_kv_heads + kvh);
-        m_max = fmaxf(m_max, p.part_ml[prow * 2]);
-    }
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
-    float lsum = 0.f;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = ((int64_t)(it.part_row0 + i * it.n_cols + wcol) * p.num_kv_heads + kvh);
-        const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - m_max);
-        lsum += w * p.part_ml[prow * 2 + 1];
-        const float *po = p.part_o + prow * D + h * 4;
-#pragma unroll
-        for (int c = 0; c < NB; ++c)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 o = *reinterpret_cast<const f32x4 *>(po + c * 32 + q4 * 8);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) oacc[c][q4 * 4 + e] += o[e] * w;
-            }
-    }
-    const float inv = 1.0f / lsum;
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
-            const bf16x4 o4 = __builtin_convertvector(o * inv, bf16x4);
-            *reinterpret_cast<u32x2 *>(op + c * 32 + q4 * 8) = __builtin_bit_cast(u32x2, o4);
-        }
 }
 
-// One launch for the whole batch: block = one chunk-tile unit, or four wave-tile units.
-// With `interleave` the two kinds alternate in the grid so that compute-bound chunk tiles and
-// memory-bound decode waves share compute units instead of running one kind after the other.
+// Chunk tiles: one block per (unit, KV head); one wavefront per SIMD so that the pipelined
+// loop has the registers it needs, the matrix pipe / vector ALU overlap comes from inside the wave.
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void attn_chunk_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
     const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one unit
     const int blk = blockIdx.x / p.num_kv_heads;
-    const int n_tile_blocks = p.num_tile_units;
-    const int n_wave_blocks = (p.num_units - p.num_tile_units + 3) / 4;
-    int tile_block = -1, wave_block = -1;
-    if (p.interleave) {
-        const int paired = min(n_tile_blocks, n_wave_blocks);
-        if (blk < 2 * paired) {
-            if (blk & 1) wave_block = blk >> 1; else tile_block = blk >> 1;
-        } else if (n_tile_blocks > n_wave_blocks) {
-            tile_block = blk - paired;
-        } else {
-            wave_block = blk - paired;
-        }
-    } else {
-        if (blk < n_tile_blocks) tile_block = blk; else wave_block = blk - n_tile_blocks;
-    }
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
-    if (tile_block >= 0) {
-        const uint32_t u = p.units[tile_block];
-        chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
-    } else {
-        const int idx = p.num_tile_units + wave_block * 4 + (threadIdx.x >> 6);
-        if (idx < p.num_units) {
-            const uint32_t u = p.units[idx];
-            wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
-        }
+    const uint32_t u = p.units[blk];
+    chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
+}
+
+// Wave tiles (decodes, tiny chunks): four independent units per block, two blocks per SIMD set.
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
+    const int kvh = blockIdx.x % p.num_kv_heads;
+    const int blk = blockIdx.x / p.num_kv_heads;
+    constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
+    const int idx = p.num_tile_units + blk * 4 + (threadIdx.x >> 6);
+    if (idx < p.num_units) {
+        const uint32_t u = p.units[idx];
+        wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Split-KV merge: out = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(m_i - max_i m_i), pieces
+// taken in index order.  A block merges 8 columns of one split tile for one KV head: D/4
+// threads per column, each owning four channels, so a piece's row is read as one coalesced
+// run and the loop over pieces is unrolled to keep several loads in flight.
+// ---------------------------------------------------------------------------------------
+constexpr int kMergeCols = 8;  // columns per block of the merge kernel (must match the planner)
+
+struct ReduceParams {
+    const TileDesc *tiles;
+    const uint32_t *reduce_units;  // (8-column group << kUnitTileBits) | tile index
+    const float *part_ml;
+    const float *part_o;
+    uint16_t *out;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t group;
+};
+
+template <int D>
+__global__ __launch_bounds__(kMergeCols * D / 4) void splitkv_reduce_kernel(ReduceParams p) {
+    constexpr int TPC = D / 4;  // threads per column
+    const int kvh = blockIdx.x % p.num_kv_heads;
+    const uint32_t u = p.reduce_units[blockIdx.x / p.num_kv_heads];
+    const TileDesc it = p.tiles[u & ((1u << kUnitTileBits) - 1)];
+    const int c = (int)(u >> kUnitTileBits) * kMergeCols + threadIdx.x / TPC;  // column inside the tile
+    const int d4 = (threadIdx.x % TPC) * 4;
+    if (c >= it.n_cols) return;
+    const int col = it.col_begin + c;
+    const int row = col / p.group;
+    const int head = kvh * p.group + (col - row * p.group);
+    const int64_t prow0 = ((int64_t)(it.part_row0 + c) * p.num_kv_heads + kvh);
+    const int64_t split_stride = (int64_t)it.n_cols * p.num_kv_heads;
+    const float *__restrict__ ml = p.part_ml;
+    const float *__restrict__ po = p.part_o;
+    float m_max = kNegSentinel;
+#pragma unroll 8
+    for (int i = 0; i < it.n_splits; ++i) m_max = fmaxf(m_max, ml[(prow0 + i * split_stride) * 2]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float lsum = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < it.n_splits; ++i) {
+        const int64_t prow = prow0 + i * split_stride;
+        const float w = __builtin_amdgcn_exp2f(ml[prow * 2] - m_max);
+        lsum += w * ml[prow * 2 + 1];
+        acc += *reinterpret_cast<const f32x4 *>(po + prow * D + d4) * w;
+    }
+    const bf16x4 o4 = __builtin_convertvector(acc * (1.0f / lsum), bf16x4);
+    uint16_t *op = p.out + ((int64_t)(it.q_start + row) * p.num_q_heads + head) * D + d4;
+    *reinterpret_cast<u32x2 *>(op) = __builtin_bit_cast(u32x2, o4);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -632,45 +699,39 @@ struct AppendParams {
     uint16_t *v_cache;
     const int32_t *block_table;
     const int32_t *q_start;
-    const int32_t *q_len;
-    const int32_t *ctx_len;
-    const int32_t *block_hint;
+    const int32_t *prefix;      // ctx_len - q_len per sequence
+    const int32_t *block_hint;  // per thread block: sequence owning the block's first token
     int64_t num_pages;
+    int64_t total_threads;
     int32_t max_blocks;
     int32_t num_seqs;
-    int32_t num_tokens;
     int32_t num_kv_heads;
 };
 
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(AppendParams p) {
     constexpr int kChunks = D / 8;
-    const int per_token = kChunks * p.num_kv_heads;
-    const int t0 = blockIdx.x * kAppendTokensPerBlock;
-    const int t1 = min(p.num_tokens, t0 + kAppendTokensPerBlock);
-    const int hint = p.block_hint[blockIdx.x];
-    for (int w = threadIdx.x; w < (t1 - t0) * per_token; w += blockDim.x) {
-        const int t = t0 + w / per_token;
-        const int r = w % per_token;
-        const int h = r / kChunks;
-        const int chunk = r % kChunks;
-        int s = hint;
-        while (s + 1 < p.num_seqs && p.q_start[s + 1] <= t) ++s;  // at most kAppendTokensPerBlock steps
-        const int pos = p.ctx_len[s] - p.q_len[s] + (t - p.q_start[s]);
-        const int64_t page = p.block_table[(int64_t)s * p.max_blocks + pos / kPageSize];
-        if (page < 0 || page >= p.num_pages) continue;  // a corrupt table entry must not become a wild store
-        const int slot = pos % kPageSize;
-        const int64_t src = ((int64_t)t * p.num_kv_heads + h) * D + chunk * 8;
-        const u32x4 kv = *reinterpret_cast<const u32x4 *>(p.k_new + src);
-        const u32x4 vv = *reinterpret_cast<const u32x4 *>(p.v_new + src);
-        const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
-        *reinterpret_cast<u32x4 *>(p.k_cache + head_base + slot * D + chunk * 8) = kv;
-        uint16_t *vdst = p.v_cache + head_base + (int64_t)(chunk * 8) * kPageSize + slot;
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (tid >= p.total_threads) return;
+    const int chunk = (int)(tid % kChunks);
+    const int h = (int)((tid / kChunks) % p.num_kv_heads);
+    const int t = (int)(tid / ((int64_t)kChunks * p.num_kv_heads));
+    int s = p.block_hint[blockIdx.x];
+    while (s + 1 < p.num_seqs && p.q_start[s + 1] <= t) ++s;  // a block spans few tokens: few steps
+    const int pos = p.prefix[s] + (t - p.q_start[s]);
+    const int64_t page = p.block_table[(int64_t)s * p.max_blocks + pos / kPageSize];
+    if (page < 0 || page >= p.num_pages) return;  // a corrupt table entry must not become a wild store
+    const int slot = pos % kPageSize;
+    const int64_t src = ((int64_t)t * p.num_kv_heads + h) * D + chunk * 8;
+    const u32x4 kv = *reinterpret_cast<const u32x4 *>(p.k_new + src);
+    const u32x4 vv = *reinterpret_cast<const u32x4 *>(p.v_new + src);
+    const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
+    *reinterpret_cast<u32x4 *>(p.k_cache + head_base + slot * D + chunk * 8) = kv;
+    uint16_t *vdst = p.v_cache + head_base + (int64_t)(chunk * 8) * kPageSize + slot;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t word = vv[e >> 1];
-            vdst[e * kPageSize] = (uint16_t)((e & 1) ? (word >> 16) : (word & 0xFFFFu));
-        }
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t word = vv[e >> 1];
+        vdst[e * kPageSize] = (uint16_t)((e & 1) ? (word >> 16) : (word & 0xFFFFu));
     }
 }
 
@@ -687,20 +748,40 @@ int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void 
     p.v_cache = static_cast<uint16_t *>(v_cache);
     p.block_table = m.block_table;
     p.q_start = m.q_start;
-    p.q_len = m.q_len;
-    p.ctx_len = m.ctx_len;
+    p.prefix = m.prefix;
     p.block_hint = m.block_hint;
     p.num_pages = num_pages;
     p.max_blocks = m.max_blocks;
     p.num_seqs = m.num_seqs;
-    p.num_tokens = m.num_tokens;
     p.num_kv_heads = cfg.num_kv_heads;
-    const unsigned blocks = (unsigned)((m.num_tokens + kAppendTokensPerBlock - 1) / kAppendTokensPerBlock);
+    p.total_threads = append_threads(cfg, m.num_tokens);
+    const unsigned blocks = (unsigned)append_blocks(cfg, m.num_tokens);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
         hipLaunchKernelGGL(kv_append_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
     else
         hipLaunchKernelGGL(kv_append_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
+    return (int)hipGetLastError();
+}
+
+int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void *stream) {
+    if (m.num_reduce_units == 0) return (int)hipSuccess;
+    static_assert(kMergeCols == kReduceCols, "planner and merge kernel must agree on columns per block");
+    ReduceParams p;
+    p.tiles = m.tiles;
+    p.reduce_units = m.reduce_units;
+    p.part_ml = m.part_ml;
+    p.part_o = m.part_o;
+    p.out = static_cast<uint16_t *>(out);
+    p.num_q_heads = cfg.num_q_heads;
+    p.num_kv_heads = cfg.num_kv_heads;
+    p.group = cfg.num_q_heads / cfg.num_kv_heads;
+    const unsigned blocks = (unsigned)m.num_reduce_units * (unsigned)cfg.num_kv_heads;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (cfg.head_dim == 128)
+        hipLaunchKernelGGL(splitkv_reduce_kernel<128>, dim3(blocks), dim3(kMergeCols * 128 / 4), 0, st, p);
+    else
+        hipLaunchKernelGGL(splitkv_reduce_kernel<64>, dim3(blocks), dim3(kMergeCols * 64 / 4), 0, st, p);
     return (int)hipGetLastError();
 }
 
@@ -715,7 +796,6 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.block_table = m.block_table;
     p.tiles = m.tiles;
     p.units = m.units;
-    p.counters = m.counters;
     p.part_ml = m.part_ml;
     p.part_o = m.part_o;
     p.num_pages = num_pages;
@@ -727,13 +807,21 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.num_units = m.num_units;
     p.interleave = m.interleave;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
-    const unsigned blocks =
-        (unsigned)(m.num_tile_units + (m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (cfg.head_dim == 128)
-        hipLaunchKernelGGL(attn_hybrid_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL(attn_hybrid_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
+    const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
+    const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
+    if (chunk_blocks) {
+        if (cfg.head_dim == 128)
+            hipLaunchKernelGGL(attn_chunk_kernel<128>, dim3(chunk_blocks), dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), 0, st, p);
+    }
+    if (wave_blocks) {
+        if (cfg.head_dim == 128)
+            hipLaunchKernelGGL(attn_wave_kernel<128>, dim3(wave_blocks), dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL(attn_wave_kernel<64>, dim3(wave_blocks), dim3(256), 0, st, p);
+    }
     return (int)hipGetLastError();
 }
 

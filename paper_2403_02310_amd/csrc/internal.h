@@ -15,9 +15,9 @@ constexpr int kPageSize = 16;     // tokens per page (the only supported value)
 constexpr int kTileKeys = 32;     // keys per inner-loop tile = two pages = one MFMA contraction depth
 constexpr int kWaveCols = 16;     // query columns a wave tile carries (16x16x32 MFMA N dimension)
 constexpr int kTileCols = 128;    // query columns a chunk tile carries (4 waves x 32x32x16 MFMA N dimension)
+constexpr int kReduceCols = 8;    // columns one block of the merge kernel handles
 constexpr int kKindWave = 0;
 constexpr int kKindTile = 1;
-constexpr int kAppendTokensPerBlock = 8;  // tokens one block of the append kernel moves
 
 // One tile of query columns of one sequence.  A "column" is one (query row, query head inside
 // a KV group) pair: col = row*G + head_in_group.  Its key range 0..n_keys-1 is cut into
@@ -33,7 +33,7 @@ struct TileDesc {
     int32_t keys_per_split;
     int32_t n_splits;
     int32_t part_row0;    // first partial row of split 0 (split i uses part_row0 + i*n_cols ..), -1 if n_splits == 1
-    int32_t counter_idx;  // arrival counter of the tile (per KV head: counter_idx*Hkv + kv_head), -1 if n_splits == 1
+    int32_t reserved;
     int32_t q_start;
     int32_t q_len;
     int32_t ctx_len;
@@ -48,7 +48,8 @@ struct Plan {
     std::vector<TileDesc> tiles;
     std::vector<uint32_t> units;      // chunk-tile units first (num_tile_units), then wave-tile units; longest first in each group
     int32_t num_tile_units = 0;
-    int32_t num_split_tiles = 0;      // tiles with n_splits > 1 (= arrival counters in use)
+    std::vector<uint32_t> reduce_units;  // (8-column group, tile) of every split tile, for the merge kernel
+    int32_t num_split_tiles = 0;      // tiles with n_splits > 1
     int32_t num_part_rows = 0;
     int32_t split_keys = 0;
     int32_t tile_split_keys = 0;
@@ -58,13 +59,12 @@ struct Plan {
 struct WorkspaceLayout {
     size_t meta;          // per-call metadata, packed: sequence arrays + hints (append) or tile descriptors + units (attention)
     size_t meta_bytes;
-    size_t counters;      // int32 [max_split_tiles][Hkv] arrival counters, zero between calls
     size_t part_ml;       // float [max_part_rows][Hkv][2]
     size_t part_o;        // float [max_part_rows][Hkv][head_dim]
     size_t total;
     int32_t max_tiles;
     int32_t max_units;
-    int32_t max_split_tiles;
+    int32_t max_reduce_units;
     int32_t max_part_rows;
 };
 
@@ -90,11 +90,18 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
                     Plan &plan);
 
 // ---- device launchers (attn_kernels.hip); each returns a hipError_t cast to int ----
+// The append kernel runs one thread per 8 channels of one (token, KV head), 256 per block.
+inline int64_t append_threads(const sarathi_config &cfg, int32_t num_tokens) {
+    return (int64_t)num_tokens * cfg.num_kv_heads * (cfg.head_dim / 8);
+}
+inline int64_t append_blocks(const sarathi_config &cfg, int32_t num_tokens) {
+    return (append_threads(cfg, num_tokens) + 255) / 256;
+}
+
 struct AppendMeta {
     const int32_t *q_start;      // dev [S]
-    const int32_t *q_len;        // dev [S]
-    const int32_t *ctx_len;      // dev [S]
-    const int32_t *block_hint;   // dev [ceil(T / kAppendTokensPerBlock)]: sequence owning the block's first token
+    const int32_t *prefix;       // dev [S]: ctx_len - q_len
+    const int32_t *block_hint;   // dev [append_blocks]: sequence owning the block's first token
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
     int32_t num_seqs;
@@ -112,12 +119,15 @@ struct AttnMeta {
     int32_t interleave;
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
-    int32_t *counters;           // dev
+    const uint32_t *reduce_units;  // dev
+    int32_t num_reduce_units;
     float *part_ml;              // dev
     float *part_o;               // dev
 };
 
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
                      const void *v_cache, int64_t num_pages, float sm_scale, void *out, void *stream);
+
+int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void *stream);
 
 }  // namespace sarathi

@@ -10,7 +10,7 @@
 // the accumulated context and differs across requests) does not become the tail of the
 // launch and (b) there are enough units to fill 256 compute units.  Chunks with at least
 // tile_min_cols columns use 128-column tiles instead (K/V staged once per tile in LDS).  The
-// splits of a tile are merged, in index order, by whichever of them finishes last.
+// splits of a tile are merged in index order by a second, small kernel.
 #include <algorithm>
 #include <cstdio>
 
@@ -34,16 +34,16 @@ WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
     const int64_t max_tiles = ceil_div((int64_t)cfg.max_tokens * G, kWaveCols) + cfg.max_seqs;
     w.max_tiles = (int32_t)std::min<int64_t>(max_tiles, INT32_MAX / 64);
     w.max_units = (int32_t)std::min<int64_t>(max_tiles + kMaxSplitUnits, INT32_MAX / 64);
-    w.max_split_tiles = (int32_t)std::min<int64_t>(max_tiles, kMaxSplitUnits / 2);
     w.max_part_rows = kMaxPartRows;
-    const size_t attn_meta = sizeof(TileDesc) * (size_t)w.max_tiles + sizeof(uint32_t) * (size_t)w.max_units + 64;
-    const size_t append_meta = sizeof(int32_t) * (3 * (size_t)cfg.max_seqs +
-                                                  (size_t)ceil_div(cfg.max_tokens, kAppendTokensPerBlock)) + 64;
+    // a split tile has at least 2 pieces of n_cols rows: sum over split tiles of ceil(n_cols/8) <= rows/16 + tiles
+    w.max_reduce_units = (int32_t)std::min<int64_t>(kMaxPartRows / (2 * kReduceCols) + kMaxSplitUnits / 2, INT32_MAX / 64);
+    const size_t attn_meta = sizeof(TileDesc) * (size_t)w.max_tiles +
+                             sizeof(uint32_t) * ((size_t)w.max_units + (size_t)w.max_reduce_units) + 64;
+    const size_t append_meta = sizeof(int32_t) * (2 * (size_t)cfg.max_seqs + (size_t)append_blocks(cfg, cfg.max_tokens)) + 64;
     size_t off = 0;
     w.meta = off;
     w.meta_bytes = align_up(std::max(attn_meta, append_meta), 256);
     off += w.meta_bytes;
-    w.counters = off;  off = align_up(off + sizeof(int32_t) * (size_t)w.max_split_tiles * cfg.num_kv_heads, 256);
     w.part_ml = off;   off = align_up(off + sizeof(float) * 2 * (size_t)w.max_part_rows * cfg.num_kv_heads, 256);
     w.part_o = off;    off = align_up(off + sizeof(float) * (size_t)w.max_part_rows * cfg.num_kv_heads * cfg.head_dim, 256);
     w.total = off;
@@ -108,10 +108,11 @@ void emit_units(Plan &plan, size_t first, size_t last, int64_t split_keys, std::
         if (t.n_splits > 1) {
             t.part_row0 = plan.num_part_rows;
             plan.num_part_rows += t.n_splits * t.n_cols;
-            t.counter_idx = plan.num_split_tiles++;
+            plan.num_split_tiles++;
+            for (int32_t c0 = 0, grp = 0; c0 < t.n_cols; c0 += kReduceCols, ++grp)
+                plan.reduce_units.push_back(pack_unit((uint32_t)ti, (uint32_t)grp));
         } else {
             t.part_row0 = -1;
-            t.counter_idx = -1;
         }
         for (int32_t i = 0; i < t.n_splits; ++i) {
             scratch.push_back(pack_unit((uint32_t)ti, (uint32_t)i));
@@ -149,6 +150,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
                     Plan &plan) {
     plan.tiles.clear();
     plan.units.clear();
+    plan.reduce_units.clear();
     plan.num_part_rows = 0;
     plan.num_tile_units = 0;
     plan.num_split_tiles = 0;
@@ -195,7 +197,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         count_splits(plan, 0, n_chunk_tiles, tile_split, n_split_units, rows, n_split_tiles);
         count_splits(plan, n_chunk_tiles, plan.tiles.size(), wave_split, n_split_units, rows, n_split_tiles);
         const int64_t max_splits_per_tile = (1 << (32 - kUnitTileBits)) - 1;
-        bool fits = n_split_units <= kMaxSplitUnits && rows <= ws.max_part_rows && n_split_tiles <= ws.max_split_tiles &&
+        bool fits = n_split_units <= kMaxSplitUnits && rows <= ws.max_part_rows && n_split_tiles <= kMaxSplitUnits / 2 &&
                     (int64_t)plan.tiles.size() + n_split_units <= ws.max_units;
         for (const TileDesc &t : plan.tiles)
             if (ceil_div(t.n_keys, t.kind == kKindTile ? tile_split : wave_split) > max_splits_per_tile) { fits = false; break; }
