@@ -49,6 +49,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "internal.h"
 
@@ -296,19 +297,28 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
 // ---------------------------------------------------------------------------------------
 // Chunk-tile path: 4 waves x 32 columns, K/V tiles of 32 keys staged in LDS.
 // ---------------------------------------------------------------------------------------
-constexpr int kRing = 4;  // LDS tile buffers of the chunk-tile path
+// LDS of the chunk-tile path: a ring of 4 K tiles and a ring of 4 V tiles (32 keys each).
+// In the step that handles tile t the wave reads K(t+1) and V(t-1) while K(t+2), K(t+3), V(t+1)
+// and V(t+2) are in flight from global memory straight into LDS (no staging registers).  Tile
+// with index rel (relative to the unit's first tile) lives in slot rel % 4 of its ring.
+constexpr int kRing = 4;
 
 template <int D>
 struct ChunkSmem {
-    static constexpr int kKStride = D + 8;                 // K rows padded by 16 bytes: conflict-free b128 reads
-    static constexpr int kKElems = kTileKeys * kKStride;   // K tile: 32 rows
-    static constexpr int kVElems = 2 * D * kPageSize;      // V tile: two pages of D x 16
-    static constexpr int kBufElems = kKElems + kVElems;
-    static constexpr int kTotalElems = kRing * kBufElems;  // ring of tiles i-1 .. i+2
+    static constexpr int kTileElems = kTileKeys * D;  // one K tile or one V tile: 32 keys x D channels
+    static constexpr int kVBase = kRing * kTileElems;
+    static constexpr int kTotalElems = 2 * kRing * kTileElems;
 };
 
+// K rows sit unpadded in LDS (a direct global->LDS load writes 1 KiB of consecutive bytes per
+// wavefront); the 16-byte chunks of row r are XOR-swizzled with this key so that the 16 lanes
+// of a b128 read, which walk 16 different rows at the same logical chunk, hit distinct banks.
+template <int D>
+__device__ __forceinline__ int k_swizzle(int r) {
+    return D == 128 ? (r & 15) : ((r >> 1) & 7);
+}
 // LDS element offset of the 8-slot half `hh` of V^T row `d` of page `u`: the two halves of a
-// row are swapped on every other group of eight channels (conflict-free writes and reads).
+// row are swapped on every other group of eight channels (conflict-free reads).
 template <int D>
 __device__ __forceinline__ int v_lds_off(int u, int d, int hh) {
     return ((u * D + d) * 2 + (hh ^ ((d >> 3) & 1))) * 8;
@@ -317,6 +327,14 @@ __device__ __forceinline__ int v_lds_off(int u, int d, int hh) {
 __device__ __forceinline__ bf16x8 lds_bf16x8(const uint16_t *p) {
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
 }
+
+typedef const void __attribute__((address_space(1))) *global_cptr;
+typedef void __attribute__((address_space(3))) *lds_ptr;
+typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
+// 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
+#define SARATHI_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
 // State a wave carries from one tile to the next in the software-pipelined chunk loop.
 template <int D>
@@ -331,79 +349,135 @@ struct ChunkState {
 
 // One pipelined step.  Independent work of three tiles shares one basic block so that the
 // matrix pipe and the vector ALU run side by side inside a single wavefront:
-//   MFMA:  O^T += V^T(t-1) P^T(t-1)      (HAS_PREV)        S^T(t+1) = K(t+1) Q^T    (HAS_NEXT)
+//   MFMA:  S^T(t+1) = K(t+1) Q^T    (HAS_NEXT)        O^T += V^T(t-1) P^T(t-1)      (HAS_PREV)
 //   VALU:  P(t) = 2^(S(t)*scale - m_ref), row sums, bf16 packing; mask and maximum of S(t+1)
+// k_chunk: this lane's (swizzled) K chunk offsets; K_OFF / V_OFF: element offsets of the ring
+// slots read in this step (wave-uniform).
 template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT>
-__device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qreg)[D / 16], const uint16_t *v_prev,
-                                           const uint16_t *k_next, float scale, int next_key0, int pos_eff) {
+__device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qreg)[D / 16], const uint16_t *smem,
+                                           const int (&k_chunk)[D / 16], int v_rd, int K_OFF, int V_OFF, float scale,
+                                           int next_key0, int pos_eff) {
     constexpr int NS = D / 16;
     constexpr int NB = D / 32;
+    constexpr int N_S = HAS_NEXT ? NS : 0;              // score MFMAs come first ...
+    constexpr int NM = N_S + (HAS_PREV ? 2 * NB : 0);   // ... then the output MFMAs
+    constexpr int AHEAD = 2;                             // operand reads run this many MFMAs ahead
+
+    // The step is laid out as NM slots fenced by scheduling barriers.  Slot i issues the LDS
+    // read for MFMA i+AHEAD, then MFMA i, then its share of the vector-ALU work, which
+    // executes while the matrix pipe is busy with MFMA i.
+    auto operand = [&](int i) -> const uint16_t * {
+        if (i < N_S) return smem + K_OFF + k_chunk[i < NS ? i : 0];
+        const int j = i - N_S;  // output MFMA j: channel block j/2, page j%2
+        return smem + v_rd + (V_OFF + ((j & 1) * D + (j >> 1) * 32) * 16);
+    };
+    bf16x8 frag[AHEAD + 1];
+#pragma unroll
+    for (int i = 0; i < AHEAD && i < NM; ++i) frag[i] = lds_bf16x8(operand(i));
+
     f32x16 s_next;
-    if (HAS_NEXT) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-            s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_bf16x8(k_next + s * 16), qreg[s], s_next, 0, 0, 0);
-    }
-    if (HAS_PREV) {
-#pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            const bf16x8 v0 = lds_bf16x8(v_prev + (c * 32) * 16);
-            const bf16x8 v1 = lds_bf16x8(v_prev + (D + c * 32) * 16);
-            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, st.p_prev[0], st.oacc[c], 0, 0, 0);
-            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, st.p_prev[1], st.oacc[c], 0, 0, 0);
-        }
-    }
-    // softmax weights of the current tile against the (already sufficient) reference
-    f32x8 p0, p1;
+    const bf16x8 p_old0 = st.p_prev[0], p_old1 = st.p_prev[1];
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    uint32_t p_new[8];  // bf16 pairs of the current tile's weights: registers (2k, 2k+1)
+    float e_even = 0.f;
     float psum = 0.f;
+    float smax = -INFINITY;
+    float neg_m = -st.m_ref;
+    auto weight = [&](int r) {
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s_cur[r], scale, neg_m));
+        psum += e;
+        if (r & 1) {
+            const bf16x2 pk = __builtin_convertvector(f32x2{e_even, e}, bf16x2);
+            p_new[r >> 1] = __builtin_bit_cast(uint32_t, pk);
+        } else {
+            e_even = e;
+        }
+    };
+    // mask + running maximum of register r of the next tile (key next_key0 + 16*(r/8) + r%8)
+    auto next_max = [&](int r) {
+        if (MASK_NEXT) s_next[r] = (next_key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? s_next[r] : -INFINITY;
+        smax = fmaxf(smax, s_next[r]);
+    };
+    constexpr int MAX_FROM = N_S + 2;  // first slot in which the finished scores may be touched
+    int w_done = 0, m_done = 0;         // compile-time after unrolling
+    // Slot boundaries.  The arithmetic below has no side effects, so nothing but data flow
+    // would keep it inside its slot; an empty asm that "touches" the values a slot produced and
+    // one input of the next slot's arithmetic (the negated reference) pins both, and the
+    // scheduling barrier keeps the machine scheduler from undoing the layout.  Neither emits
+    // an instruction.
+    asm volatile("" : "+v"(neg_m), "+v"(psum));
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        p0[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s_cur[j], scale, -st.m_ref));
-        p1[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s_cur[8 + j], scale, -st.m_ref));
-        psum += p0[j] + p1[j];
-    }
-    st.l_run += psum;
-    st.p_prev[0] = __builtin_convertvector(p0, bf16x8);
-    st.p_prev[1] = __builtin_convertvector(p1, bf16x8);
-    if (HAS_NEXT) {
-        // register r of lane (h, n): key next_key0 + 16*(r/8) + r%8 , column n
-        if (MASK_NEXT) {
+    for (int i = 0; i < NM; ++i) {
+        bf16x8 &ahead = frag[(i + AHEAD) % (AHEAD + 1)];
+        if (i + AHEAD < NM) ahead = lds_bf16x8(operand(i + AHEAD));
+        const bf16x8 a = frag[i % (AHEAD + 1)];
+        if (i < N_S) {
+            if (i == 0) {
+                f32x16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0], zero, 0, 0, 0);
+            } else {
+                s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[i < NS ? i : 0], s_next, 0, 0, 0);
+            }
+        } else {
+            const int j = i - N_S;
+            st.oacc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, (j & 1) ? p_old1 : p_old0, st.oacc[j >> 1], 0, 0, 0);
+        }
+        // vector-ALU share of this slot
+        const int w_from = w_done;
+        const int w_target = 16 * (i + 1) / (NM > 0 ? NM : 1);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (r >= w_from && r < w_target) weight(r);
+        w_done = w_target;
+        if (HAS_NEXT && i >= MAX_FROM) {
+            const int m_target = 16 * (i + 1 - MAX_FROM) / (NM > MAX_FROM ? NM - MAX_FROM : 1);
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                s_next[r] = (next_key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? s_next[r] : -INFINITY;
+                if (r >= m_done && r < m_target) next_max(r);
+            m_done = m_target;
         }
-        float smax = s_next[0];
+        // pin: this slot's MFMA result, the operand fetched ahead, the weights made here
+        if (i < N_S)
+            asm volatile("" : "+v"(s_next), "+v"(ahead), "+v"(neg_m), "+v"(psum), "+v"(e_even));
+        else
+            asm volatile("" : "+v"(st.oacc[(i - N_S) >> 1]), "+v"(ahead), "+v"(neg_m), "+v"(psum), "+v"(e_even), "+v"(s_next), "+v"(smax));
 #pragma unroll
-        for (int r = 1; r < 16; ++r) smax = fmaxf(smax, s_next[r]);
+        for (int r = 1; r < 16; r += 2)
+            if (r >= w_from && r < w_target) asm volatile("" : "+v"(p_new[r >> 1]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // whatever did not fit into the slots (steps without MFMAs, or too few of them)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (r >= w_done) weight(r);
+    if (HAS_NEXT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (r >= m_done) next_max(r);
         smax = fmaxf(smax, __shfl_xor(smax, 32));
         st.tmax = smax * scale;  // scale > 0
         st.s_cur = s_next;
     }
-    // Issue order: every MFMA is followed by one LDS operand read and a few vector-ALU
-    // instructions, which execute while the matrix pipe works on that MFMA.
-    constexpr int kMfma = (HAS_PREV ? 2 * NB : 0) + (HAS_NEXT ? NS : 0);
-    if (kMfma > 0) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // two operand reads ahead
-#pragma unroll
-        for (int i = 0; i < kMfma; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // VALU
-        }
-    }
+    st.l_run += psum;
+    typedef __attribute__((ext_vector_type(4))) uint32_t pk4;
+    st.p_prev[0] = __builtin_bit_cast(bf16x8, pk4{p_new[0], p_new[1], p_new[2], p_new[3]});
+    st.p_prev[1] = __builtin_bit_cast(bf16x8, pk4{p_new[4], p_new[5], p_new[6], p_new[7]});
 }
 
 template <int D>
 __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileDesc &it, int split, int kvh,
                                                 uint16_t *smem) {
-    constexpr int NS = D / 16;         // contraction steps of the score MFMAs
-    constexpr int NB = D / 32;         // 32-channel blocks of the output
-    constexpr int PER_THREAD = D / 64; // 16-byte chunks each thread stages per K (and per V) tile
-    constexpr int PAGE_CHUNKS = 2 * D; // 16-byte chunks of one page of one KV head
-    constexpr int CPR = D / 8;         // 16-byte chunks per K row
+    constexpr int NS = D / 16;            // contraction steps of the score MFMAs
+    constexpr int NB = D / 32;            // 32-channel blocks of the output
+    constexpr int CPR = D / 8;            // 16-byte chunks per K row
+    constexpr int PAGE_ELEMS = kPageSize * D;
+    constexpr int LOADS_PER_PAGE = PAGE_ELEMS / 512;  // 1 KiB wavefront loads per page of one KV head
     using SM = ChunkSmem<D>;
+    constexpr int TE = SM::kTileElems;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; tell the compiler
@@ -424,7 +498,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     const int head = kvh * G + (col - row * G);
     const int pos_eff = min(prefix + row, ur.key_end - 1);
     const int wave_first_col = it.col_begin + ((wave * 32 < it.n_cols) ? wave * 32 : 0);
-    const int min_pos_eff = min(prefix + wave_first_col / G, ur.key_end - 1);
+    const int min_pos_eff = min(prefix + wave_first_col / G, ur.key_end - 1);  // wave-uniform
 
     bf16x8 qreg[NS];  // B operand of the score MFMAs: column n, channels 16s + 8h ..
     {
@@ -433,54 +507,42 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         for (int s = 0; s < NS; ++s) qreg[s] = load_bf16x8(qp + s * 16);
     }
 
-    const int32_t *bt = p.block_table + (int64_t)seq * p.max_blocks;
+    // Global -> LDS traffic of a tile: wave 0/1 move K page 0/1, wave 2/3 move V page 0/1, each
+    // as LOADS_PER_PAGE direct loads of 1 KiB.  Lane l of load j fills physical 16-byte chunk
+    // q = 64j + l of the page's LDS image and therefore fetches the logical chunk that lives there.
+    // K pages run three tiles ahead of the step, V pages two (V is consumed two steps later than K).
+    const bool moves_v = wave >= 2;
+    const int my_page = wave & 1;
+    int g_off[LOADS_PER_PAGE];  // element offset inside the page of one KV head
+#pragma unroll
+    for (int j = 0; j < LOADS_PER_PAGE; ++j) {
+        const int q = j * 64 + lane;
+        const int k_slot = q / CPR;
+        const int k_elem = k_slot * D + ((q % CPR) ^ k_swizzle<D>(k_slot)) * 8;
+        const int v_d = q >> 1;
+        const int v_elem = (v_d * 2 + ((q & 1) ^ ((v_d >> 3) & 1))) * 8;
+        g_off[j] = moves_v ? v_elem : k_elem;
+    }
+    const const_i32_ptr bt = (const_i32_ptr)(p.block_table + (int64_t)seq * p.max_blocks);  // read-only: scalar loads
     const int n_pages_seq = (ctx + kPageSize - 1) / kPageSize;
     const int64_t page_stride = (int64_t)p.num_kv_heads * kPageSize * D;
-    const int64_t head_off = (int64_t)kvh * kPageSize * D;
+    const uint16_t *cache_head = (moves_v ? p.v_cache : p.k_cache) + (int64_t)kvh * PAGE_ELEMS;
     const int64_t last_page_id = p.num_pages - 1;
-
-    // Staging: chunk index idx = tid + 256*j of the tile; page u = idx / PAGE_CHUNKS.  The LDS
-    // destinations do not depend on the tile, so they are computed once.
-    u32x4 kst[PER_THREAD], vst[PER_THREAD];
-    int st_k_off[PER_THREAD], st_v_off[PER_THREAD];
+    const int tile_begin = ur.key_begin / kTileKeys;
+    const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
+    const int n_tiles = tile_end - tile_begin;
+    const int my_lds_base = (moves_v ? SM::kVBase : 0) + my_page * PAGE_ELEMS;
+    // this wave's page of tile `tile` -> ring slot (tile - tile_begin) % 4
+    auto issue_tile = [&](int tile) {
+        int64_t pg = bt[min(tile * 2 + my_page, n_pages_seq - 1)];
+        pg = pg < 0 ? 0 : (pg > last_page_id ? last_page_id : pg);
+        const uint16_t *src = cache_head + pg * page_stride;
+        uint16_t *dst = smem + my_lds_base + ((tile - tile_begin) & (kRing - 1)) * TE;
 #pragma unroll
-    for (int j = 0; j < PER_THREAD; ++j) {
-        const int idx = tid + 256 * j;
-        const int u = idx / PAGE_CHUNKS;
-        const int i = idx % PAGE_CHUNKS;
-        st_k_off[j] = (u * kPageSize + i / CPR) * SM::kKStride + (i % CPR) * 8;  // slot i/CPR, chunk i%CPR
-        st_v_off[j] = SM::kKElems + v_lds_off<D>(u, i >> 1, i & 1);              // channel i/2, slots 8*(i%2)..
-    }
-    auto issue_loads = [&](int tile) {
-#pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) {
-            const int idx = tid + 256 * j;
-            const int u = idx / PAGE_CHUNKS;
-            const int i = idx % PAGE_CHUNKS;
-            int64_t pg = bt[min(tile * 2 + u, n_pages_seq - 1)];
-            pg = pg < 0 ? 0 : (pg > last_page_id ? last_page_id : pg);
-            const int64_t base = pg * page_stride + head_off + (int64_t)i * 8;
-            kst[j] = *reinterpret_cast<const u32x4 *>(p.k_cache + base);
-            vst[j] = *reinterpret_cast<const u32x4 *>(p.v_cache + base);
-        }
+        for (int j = 0; j < LOADS_PER_PAGE; ++j)
+            __builtin_amdgcn_global_load_lds((global_cptr)(src + g_off[j]), (lds_ptr)(dst + j * 512), 16, 0, 0);
     };
-    auto commit = [&](int tile, int buf) {
-        uint16_t *bb = smem + buf * SM::kBufElems;
-        const bool tail = tile * kTileKeys + kTileKeys > ctx;  // tile holds slots at or beyond ctx_len
-#pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) {
-            *reinterpret_cast<u32x4 *>(bb + st_k_off[j]) = kst[j];
-            u32x4 v = vst[j];
-            if (tail) {
-                const int idx = tid + 256 * j;
-                const int key0 = tile * kTileKeys + (idx / PAGE_CHUNKS) * kPageSize + (idx & 1) * 8;
-#pragma unroll
-                for (int w = 0; w < 4; ++w)
-                    v[w] &= ((key0 + 2 * w < ctx) ? 0x0000FFFFu : 0u) | ((key0 + 2 * w + 1 < ctx) ? 0xFFFF0000u : 0u);
-            }
-            *reinterpret_cast<u32x4 *>(bb + st_v_off[j]) = v;
-        }
-    };
+    const int my_ahead = moves_v ? 2 : 3;  // tiles this wave's loads run ahead of the step
 
     ChunkState<D> st;
 #pragma unroll
@@ -489,45 +551,48 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         for (int r = 0; r < 16; ++r) st.oacc[c][r] = 0.f;
     st.m_ref = kNegSentinel;
     st.l_run = 0.f;
+    st.tmax = kNegSentinel;
 
     // MFMA row n of the score tile is key  16u + 8h' + 4a + b  for n = 16u + 8a + 4h' + b.
     const int k_row = (n & 16) | ((n & 4) << 1) | ((n & 8) >> 1) | (n & 3);
-    const int k_rd = k_row * SM::kKStride + h * 8;          // + 16*s elements for contraction step s
-    const int v_rd = SM::kKElems + v_lds_off<D>(0, n, h);   // + (u*D + 32c)*16 elements for page u, channel block c
+    int k_chunk[NS];  // element offset of contraction step s inside this lane's K row (swizzled)
+#pragma unroll
+    for (int s = 0; s < NS; ++s) k_chunk[s] = k_row * D + ((s * 2 + h) ^ k_swizzle<D>(k_row)) * 8;
+    const int v_rd = SM::kVBase + v_lds_off<D>(0, n, h);  // + slot*TE + (u*D + 32c)*16 elements
     const float scale = p.scale_log2;
+    // first tile of the range in which some column of this wave needs masking (wave-uniform)
+    const int mask_from = max(tile_begin, min(tile_end, (min_pos_eff + 1) / kTileKeys));
 
-    const int tile_begin = ur.key_begin / kTileKeys;
-    const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
-    auto needs_mask = [&](int tile) { return tile * kTileKeys + (kTileKeys - 1) > min_pos_eff; };  // wave-uniform
-
-    // Prologue: tiles 0 and 1 of the range go to LDS, tile 2 into the staging registers, and
-    // the scores of tile 0 are formed (as the "next" tile of an otherwise empty step).
-    issue_loads(tile_begin);
-    commit(tile_begin, 0);
-    if (tile_begin + 1 < tile_end) {
-        issue_loads(tile_begin + 1);
-        commit(tile_begin + 1, 1);
-    }
-    if (tile_begin + 2 < tile_end) issue_loads(tile_begin + 2);
-    __syncthreads();
+    // Prologue: the first tiles start loading; when they have landed the scores of tile 0 are
+    // formed (as the "next" tile of an otherwise empty step).
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        if (i < my_ahead && i < n_tiles) issue_tile(tile_begin + i);
+    SARATHI_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     {
 #pragma unroll
         for (int r = 0; r < 16; ++r) st.s_cur[r] = -INFINITY;  // "current" tile of the empty step: weights 0
         st.p_prev[0] = st.p_prev[1] = bf16x8{};
-        const uint16_t *k0 = smem + k_rd;
         const int key0 = tile_begin * kTileKeys + h * 8;
-        if (needs_mask(tile_begin))
-            chunk_step<D, false, true, true>(st, qreg, nullptr, k0, scale, key0, pos_eff);
+        if (tile_begin >= mask_from)
+            chunk_step<D, false, true, true>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
         else
-            chunk_step<D, false, true, false>(st, qreg, nullptr, k0, scale, key0, pos_eff);
+            chunk_step<D, false, true, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
         st.l_run = 0.f;  // the empty step contributed exp2(-inf) = 0 terms only
     }
 
-    for (int tile = tile_begin; tile < tile_end; ++tile) {
-        const int rel = tile - tile_begin;
-        // staging: tile+2 (loaded during the previous step) enters the ring; tile+3 starts loading
-        if (tile + 2 < tile_end) commit(tile + 2, (rel + 2) & (kRing - 1));
-        if (tile + 3 < tile_end) issue_loads(tile + 3);
+    // Common head of a step for tile t, then the step proper.  Every loop below instantiates one
+    // variant only, so its body stays a single basic block (plus the rare reference raise).
+    auto step = [&](int tile, auto has_prev, auto has_next, auto mask_next) {
+        // Tile t+1 must have landed (only this wave's loads of one later tile may still be in
+        // flight), and every wave must be done with the slots about to be overwritten (K of
+        // tile t-1, V of tile t-2).
+        if (tile + my_ahead - 1 < tile_end) SARATHI_WAIT_VMCNT(LOADS_PER_PAGE); else SARATHI_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (tile + my_ahead < tile_end) issue_tile(tile + my_ahead);
         // raise the softmax reference if this tile exceeds it by more than the slack (rare)
         if (__any(st.tmax > st.m_ref + kRescaleSlack)) {
             const float m_new = fmaxf(st.m_ref, st.tmax);
@@ -537,38 +602,47 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
 #pragma unroll
             for (int c = 0; c < NB; ++c) st.oacc[c] *= alpha;
         }
-        const uint16_t *v_prev = smem + ((rel - 1) & (kRing - 1)) * SM::kBufElems + v_rd;
-        const uint16_t *k_next = smem + ((rel + 1) & (kRing - 1)) * SM::kBufElems + k_rd;
+        const int rel = tile - tile_begin;
         const int next_key0 = (tile + 1) * kTileKeys + h * 8;
-        const bool has_prev = tile > tile_begin;
-        const bool has_next = tile + 1 < tile_end;
-        if (has_prev && has_next) {
-            if (needs_mask(tile + 1))
-                chunk_step<D, true, true, true>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
-            else
-                chunk_step<D, true, true, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
-        } else if (has_next) {
-            if (needs_mask(tile + 1))
-                chunk_step<D, false, true, true>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
-            else
-                chunk_step<D, false, true, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
-        } else if (has_prev) {
-            chunk_step<D, true, false, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
-        } else {
-            chunk_step<D, false, false, false>(st, qreg, v_prev, k_next, scale, next_key0, pos_eff);
-        }
-        __syncthreads();
+        chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value>(
+            st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE, ((rel + 3) & (kRing - 1)) * TE, scale,
+            next_key0, pos_eff);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    if (n_tiles == 1) {
+        step(tile_begin, F{}, F{}, F{});
+    } else {
+        // first tile: nothing to accumulate yet
+        if (tile_begin + 1 >= mask_from) step(tile_begin, F{}, T{}, T{}); else step(tile_begin, F{}, T{}, F{});
+        // steady state: unmasked tiles, then the tiles on the causal diagonal
+        int tile = tile_begin + 1;
+        for (; tile + 1 < tile_end && tile + 1 < mask_from; ++tile) step(tile, T{}, T{}, F{});
+        for (; tile + 1 < tile_end; ++tile) step(tile, T{}, T{}, T{});
+        // last tile: no further scores to form
+        step(tile_end - 1, T{}, F{}, F{});
     }
-    // Epilogue: the output MFMAs of the last tile.
+    // Epilogue: the output MFMAs of the last tile.  Only here can a tile hold slots at or beyond
+    // ctx_len (a unit never extends past the sequence), whose V bits must be zeroed: stale cache
+    // contents times a zero weight would still poison the accumulator if they were NaN or Inf.
     {
-        const int rel = tile_end - 1 - tile_begin;
-        const uint16_t *v_last = smem + (rel & (kRing - 1)) * SM::kBufElems + v_rd;
+        const int last = tile_end - 1;
+        const uint16_t *v_last = smem + v_rd + ((last - tile_begin) & (kRing - 1)) * TE;
+        const bool tail = last * kTileKeys + kTileKeys > ctx;
 #pragma unroll
         for (int c = 0; c < NB; ++c) {
-            const bf16x8 v0 = lds_bf16x8(v_last + (c * 32) * 16);
-            const bf16x8 v1 = lds_bf16x8(v_last + (D + c * 32) * 16);
-            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, st.p_prev[0], st.oacc[c], 0, 0, 0);
-            st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, st.p_prev[1], st.oacc[c], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                u32x4 v = *reinterpret_cast<const u32x4 *>(v_last + (u * D + c * 32) * 16);
+                if (tail) {
+                    const int key0 = last * kTileKeys + u * kPageSize + h * 8;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        v[w] &= ((key0 + 2 * w < ctx) ? 0x0000FFFFu : 0u) | ((key0 + 2 * w + 1 < ctx) ? 0xFFFF0000u : 0u);
+                }
+                st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), st.p_prev[u],
+                                                                      st.oacc[c], 0, 0, 0);
+            }
         }
     }
     f32x16 (&oacc)[NB] = st.oacc;
