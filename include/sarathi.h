@@ -94,7 +94,7 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * 16-column wave tiles, multiple of 32, 0 = automatic), "target_items" (items the automatic
  * choice aims for), "tile_split_keys" / "tile_target_items" (the same for 128-column chunk
  * tiles), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
- * tiles), "interleave" (0/1: alternate chunk-tile and wave-tile blocks in the launch),
+ * tiles), "interleave" (0/1: run the chunk-tile kernel on a second stream next to the wave-tile kernel),
  * "time_kernels" (0/1, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);

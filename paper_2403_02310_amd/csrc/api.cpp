@@ -34,6 +34,10 @@ struct sarathi_handle {
     size_t staging_bytes = 0;
     int next_slot = 0;
     bool staging_ready = false;
+    // Second stream (default priority) on which the chunk-tile kernel runs next to the wave-tile
+    // kernel, and the events that fork it from / join it into the caller's stream.
+    hipStream_t side_stream = nullptr;
+    hipEvent_t fork_event = nullptr, join_event = nullptr;
     // Optional per-kernel timing: event pairs recorded around each launch.
     bool time_kernels = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, merge
@@ -133,6 +137,12 @@ extern "C" sarathi_status sarathi_destroy(sarathi_handle *h) {
     }
     for (auto &pool : h->timing_pool)
         for (auto &pr : pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+    if (h->side_stream) {
+        (void)hipStreamSynchronize(h->side_stream);
+        (void)hipStreamDestroy(h->side_stream);
+    }
+    if (h->fork_event) (void)hipEventDestroy(h->fork_event);
+    if (h->join_event) (void)hipEventDestroy(h->join_event);
     delete h;
     return SARATHI_OK;
 }
@@ -335,15 +345,34 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.units = reinterpret_cast<const uint32_t *>(dev + units_off);
     m.num_tile_units = pl.num_tile_units;
     m.num_units = (int32_t)pl.units.size();
-    m.interleave = (int32_t)h->opt.interleave;
     m.block_table = block_table;
     m.max_blocks = h->cfg.max_blocks_per_seq;
     m.reduce_units = reinterpret_cast<const uint32_t *>(dev + reduce_off);
     m.num_reduce_units = (int32_t)pl.reduce_units.size();
     m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
+    // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
+    // has both they run side by side: the chunk kernel is forked onto a second stream.
+    const bool both = pl.num_tile_units > 0 && (int32_t)pl.units.size() > pl.num_tile_units && h->opt.interleave;
+    if (both && !h->side_stream) {
+        e = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) return hip_fail(h, "hipStreamCreate(side)", e);
+        e = hipEventCreateWithFlags(&h->fork_event, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&h->join_event, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(h, "hipEventCreate(fork/join)", e);
+    }
     const int t1 = timing_begin(h, 1, s);
-    e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, stream);
+    if (both) {
+        e = hipEventRecord(h->fork_event, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(h->side_stream, h->fork_event, 0);
+        if (e != hipSuccess) return hip_fail(h, "fork to side stream", e);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1, h->side_stream);
+        if (e == hipSuccess) e = hipEventRecord(h->join_event, h->side_stream);
+        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, h->join_event, 0);
+    } else {
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, stream);
+    }
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);
     if (m.num_reduce_units > 0) {

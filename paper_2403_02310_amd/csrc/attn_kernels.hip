@@ -79,7 +79,6 @@ struct AttnParams {
     int32_t group;
     int32_t num_tile_units;  // units [0, num_tile_units) are 128-column chunk tiles (one block each)
     int32_t num_units;       // the rest are 16-column wave tiles (four per block)
-    int32_t interleave;      // alternate the two kinds of block in the grid
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
 };
 
@@ -860,7 +859,7 @@ int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void 
 }
 
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, void *stream) {
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream) {
     if (m.num_units == 0) return (int)hipSuccess;
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
@@ -879,18 +878,17 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.group = cfg.num_q_heads / cfg.num_kv_heads;
     p.num_tile_units = m.num_tile_units;
     p.num_units = m.num_units;
-    p.interleave = m.interleave;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
     const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
-    if (chunk_blocks) {
+    if (chunk_blocks && (which & 1)) {
         if (cfg.head_dim == 128)
             hipLaunchKernelGGL(attn_chunk_kernel<128>, dim3(chunk_blocks), dim3(256), 0, st, p);
         else
             hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), 0, st, p);
     }
-    if (wave_blocks) {
+    if (wave_blocks && (which & 2)) {
         if (cfg.head_dim == 128)
             hipLaunchKernelGGL(attn_wave_kernel<128>, dim3(wave_blocks), dim3(256), 0, st, p);
         else

@@ -74,7 +74,7 @@ struct Options {
     int64_t tile_split_keys = 0;    // the same two knobs for the 128-column chunk tiles
     int64_t tile_target_items = 96;
     int64_t tile_min_cols = 64;     // sequences with fewer columns (q_len*G) use wave tiles only
-    int64_t interleave = 1;         // alternate chunk-tile blocks and wave-tile blocks in the grid
+    int64_t interleave = 1;         // run the chunk-tile kernel on a second stream next to the wave-tile kernel
 };
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg);
@@ -116,7 +116,6 @@ struct AttnMeta {
     const uint32_t *units;       // dev
     int32_t num_tile_units;
     int32_t num_units;
-    int32_t interleave;
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
     const uint32_t *reduce_units;  // dev
@@ -125,8 +124,9 @@ struct AttnMeta {
     float *part_o;               // dev
 };
 
+// which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, void *stream);
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream);
 
 int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void *stream);
 
