@@ -92,9 +92,10 @@ const char *sarathi_last_error(const sarathi_handle *handle);
 
 /* Tuning knobs, all optional: "split_keys" (target keys per split-KV work item of the
  * 16-column wave tiles, multiple of 32, 0 = automatic), "target_items" (items the automatic
- * choice aims for), "tile_split_keys" / "tile_target_items" (the same for 128-column chunk
- * tiles), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
- * tiles), "interleave" (0/1: run the chunk-tile kernel on a second stream next to the wave-tile kernel),
+ * choice aims for), "tile_split_keys" (keys per split of the 128-column chunk tiles, 0 =
+ * automatic), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
+ * tiles), "plan_at_append" (0/1: sarathi_kv_append also plans and uploads the attention
+ * metadata of its batch so that the following attention call needs no copy of its own), "interleave" (0/1: run the chunk-tile kernel on a second stream next to the wave-tile kernel),
  * "time_kernels" (0/1, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);

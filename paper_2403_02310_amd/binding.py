@@ -13,7 +13,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsarathi.so")
+LIB_PATH = os.environ.get("SARATHI_LIB", os.path.join(_HERE, "libsarathi.so"))  # override: A/B builds of the same sources
 
 OK, EINVAL, ESHAPE, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
 STATUS_NAMES = {0: "SARATHI_OK", -1: "SARATHI_EINVAL", -2: "SARATHI_ESHAPE", -3: "SARATHI_ECAPACITY",

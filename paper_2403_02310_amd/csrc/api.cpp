@@ -34,6 +34,15 @@ struct sarathi_handle {
     size_t staging_bytes = 0;
     int next_slot = 0;
     bool staging_ready = false;
+    // Attention metadata uploaded ahead of time by sarathi_kv_append: the iteration's attention
+    // call gets the same description, so its plan rides along in the append's copy.  Valid while
+    // `resident_*` describe what the metadata region of `resident_ws` holds.
+    void *resident_ws = nullptr;
+    void *resident_stream = nullptr;
+    std::vector<int32_t> resident_desc;  // q_len | ctx_len of the planned batch
+    uint64_t resident_opt_version = 0;
+    uint64_t opt_version = 1;
+    size_t resident_attn_off = 0;        // byte offset of the attention metadata inside the region
     // Second stream (default priority) on which the chunk-tile kernel runs next to the wave-tile
     // kernel, and the events that fork it from / join it into the caller's stream.
     hipStream_t side_stream = nullptr;
@@ -102,6 +111,31 @@ void timing_end(sarathi_handle *h, int kind, int idx, hipStream_t s) {
     if (hipEventRecord(h->timing_pool[kind][idx].second, s) == hipSuccess) h->timing_used[kind] = (size_t)idx + 1;
 }
 
+// Attention metadata, packed back to back at `dst`: tile descriptors, work units, merge units.
+struct AttnMetaOffsets {
+    size_t units, reduce, total;
+};
+AttnMetaOffsets attn_meta_offsets(const Plan &pl) {
+    AttnMetaOffsets o;
+    o.units = align_up(sizeof(TileDesc) * pl.tiles.size(), 16);
+    o.reduce = o.units + sizeof(uint32_t) * pl.units.size();
+    o.total = align_up(o.reduce + sizeof(uint32_t) * pl.reduce_units.size(), 16);
+    return o;
+}
+void pack_attn_meta(char *dst, const Plan &pl, const AttnMetaOffsets &o) {
+    std::memcpy(dst, pl.tiles.data(), sizeof(TileDesc) * pl.tiles.size());
+    std::memcpy(dst + o.units, pl.units.data(), sizeof(uint32_t) * pl.units.size());
+    std::memcpy(dst + o.reduce, pl.reduce_units.data(), sizeof(uint32_t) * pl.reduce_units.size());
+}
+
+bool resident_plan_matches(const sarathi_handle *h, const int32_t *q_len, const int32_t *ctx_len, int32_t n,
+                           const void *workspace, const void *stream) {
+    if (h->resident_ws != workspace || h->resident_stream != stream || h->resident_opt_version != h->opt_version) return false;
+    if (h->resident_desc.size() != 2 * (size_t)n) return false;
+    return std::memcmp(h->resident_desc.data(), q_len, sizeof(int32_t) * (size_t)n) == 0 &&
+           std::memcmp(h->resident_desc.data() + n, ctx_len, sizeof(int32_t) * (size_t)n) == 0;
+}
+
 }  // namespace
 
 extern "C" sarathi_status sarathi_create(const sarathi_config *config, sarathi_handle **out) {
@@ -153,6 +187,7 @@ extern "C" const char *sarathi_last_error(const sarathi_handle *h) { return h ? 
 
 extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name, int64_t value) {
     if (!h || !name) return SARATHI_EINVAL;
+    h->opt_version++;  // a resident plan made under the old options is not reused
     if (std::strcmp(name, "split_keys") == 0) {
         if (value < 0 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "split_keys out of range");
         h->opt.split_keys = value;
@@ -168,14 +203,13 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.tile_split_keys = value;
         return SARATHI_OK;
     }
-    if (std::strcmp(name, "tile_target_items") == 0) {
-        if (value < 1 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "tile_target_items out of range");
-        h->opt.tile_target_items = value;
-        return SARATHI_OK;
-    }
     if (std::strcmp(name, "tile_min_cols") == 0) {
         if (value < 1 || value > (1 << 30)) return fail(h, SARATHI_EINVAL, "tile_min_cols out of range");
         h->opt.tile_min_cols = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "plan_at_append") == 0) {
+        h->opt.plan_at_append = value != 0;
         return SARATHI_OK;
     }
     if (std::strcmp(name, "interleave") == 0) {
@@ -219,6 +253,7 @@ extern "C" sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *h, const
     if (!info) return fail(h, SARATHI_EINVAL, "null info");
     sarathi_status st = validate_batch(h->cfg, q_start, q_len, ctx_len, num_seqs, num_tokens, 1, h->err);
     if (st != SARATHI_OK) return st;
+    h->resident_ws = nullptr;  // h->plan is about to be overwritten
     plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
     const Plan &pl = h->plan;
     info->num_items = (int32_t)pl.units.size();
@@ -274,13 +309,32 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
         while (sq + 1 < num_seqs && q_start[sq + 1] <= t) ++sq;
         hint[b] = (int32_t)sq;
     }
-    const size_t used = sizeof(int32_t) * (2 * n + (size_t)n_blocks);
+    size_t used = sizeof(int32_t) * (2 * n + (size_t)n_blocks);
     if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
+    // The attention call of this iteration will get the same description: plan it now and let
+    // its metadata ride along in this copy (one host-to-device copy per iteration instead of two).
+    h->resident_ws = nullptr;
+    if (h->opt.plan_at_append) {
+        plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
+        const AttnMetaOffsets o = attn_meta_offsets(h->plan);
+        const size_t attn_off = align_up(used, 256);
+        if (attn_off + o.total <= h->staging_bytes) {
+            pack_attn_meta(reinterpret_cast<char *>(host) + attn_off, h->plan, o);
+            used = attn_off + o.total;
+            h->resident_attn_off = attn_off;
+            h->resident_desc.resize(2 * n);
+            std::memcpy(h->resident_desc.data(), q_len, sizeof(int32_t) * n);
+            std::memcpy(h->resident_desc.data() + n, ctx_len, sizeof(int32_t) * n);
+            h->resident_opt_version = h->opt_version;
+            h->resident_stream = stream;
+            h->resident_ws = workspace;
+        }
+    }
 
     char *dev = static_cast<char *>(workspace) + h->ws.meta;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
+    if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "hipMemcpyAsync(metadata)", e); }
     e = hipEventRecord(h->staged[slot], s);
     if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
     h->in_flight[slot] = true;
@@ -313,32 +367,33 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     if (!q || !k_cache || !v_cache || !block_table || !out) return fail(h, SARATHI_EINVAL, "null tensor pointer");
     if (!(sm_scale > 0.0f) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale must be positive and finite");
     if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
-    plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
-    const Plan &pl = h->plan;
-    if ((st = ensure_staging(h)) != SARATHI_OK) return st;
-    int slot;
-    if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
-
     char *ws = static_cast<char *>(workspace);
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-
-    // Metadata packed back to back: tile descriptors, work units, merge units; one copy.
-    char *host = static_cast<char *>(h->staging[slot]);
-    const size_t tiles_bytes = sizeof(TileDesc) * pl.tiles.size();
-    const size_t units_off = align_up(tiles_bytes, 16);
-    const size_t reduce_off = units_off + sizeof(uint32_t) * pl.units.size();
-    const size_t used = reduce_off + sizeof(uint32_t) * pl.reduce_units.size();
-    if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
-    std::memcpy(host, pl.tiles.data(), tiles_bytes);
-    std::memcpy(host + units_off, pl.units.data(), sizeof(uint32_t) * pl.units.size());
-    std::memcpy(host + reduce_off, pl.reduce_units.data(), sizeof(uint32_t) * pl.reduce_units.size());
-    char *dev = ws + h->ws.meta;
-    e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
-    e = hipEventRecord(h->staged[slot], s);
-    if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
-    h->in_flight[slot] = true;
+    char *dev;
+    if (resident_plan_matches(h, q_len, ctx_len, num_seqs, workspace, stream)) {
+        // planned and uploaded by the sarathi_kv_append of this iteration (h->plan is that plan)
+        dev = ws + h->ws.meta + h->resident_attn_off;
+    } else {
+        plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
+        if ((st = ensure_staging(h)) != SARATHI_OK) return st;
+        int slot;
+        if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
+        const AttnMetaOffsets o = attn_meta_offsets(h->plan);
+        if (o.total > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
+        char *host = static_cast<char *>(h->staging[slot]);
+        pack_attn_meta(host, h->plan, o);
+        dev = ws + h->ws.meta;
+        h->resident_ws = nullptr;  // the region no longer holds what an earlier append put there
+        e = hipMemcpyAsync(dev, host, o.total, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
+        e = hipEventRecord(h->staged[slot], s);
+        if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
+        h->in_flight[slot] = true;
+    }
+    const Plan &pl = h->plan;
+    const AttnMetaOffsets mo = attn_meta_offsets(pl);
+    const size_t units_off = mo.units, reduce_off = mo.reduce;
 
     AttnMeta m;
     m.tiles = reinterpret_cast<const TileDesc *>(dev);

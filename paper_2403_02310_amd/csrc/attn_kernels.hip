@@ -358,17 +358,31 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
                                            int next_key0, int pos_eff) {
     constexpr int NS = D / 16;
     constexpr int NB = D / 32;
-    constexpr int N_S = HAS_NEXT ? NS : 0;              // score MFMAs come first ...
-    constexpr int NM = N_S + (HAS_PREV ? 2 * NB : 0);   // ... then the output MFMAs
-    constexpr int AHEAD = 2;                             // operand reads run this many MFMAs ahead
+    constexpr int N_S = HAS_NEXT ? NS : 0;              // score MFMAs (one dependent chain through s_next)
+    constexpr int N_O = HAS_PREV ? 2 * NB : 0;          // output MFMAs (NB accumulators, two pages each)
+    constexpr int NM = N_S + N_O;
+#ifndef SARATHI_AHEAD
+#define SARATHI_AHEAD 3
+#endif
+    constexpr int AHEAD = SARATHI_AHEAD;                 // operand reads run this many MFMAs ahead
+    // MFMA order: score and output MFMAs alternate while both kinds last, so that an MFMA never
+    // follows the one whose accumulator it needs (the score chain is dependent, and so are the
+    // two pages of one output block); the output MFMAs go page-major for the same reason.
+#ifndef SARATHI_MFMA_ALTERNATE
+#define SARATHI_MFMA_ALTERNATE 1
+#endif
+    constexpr int N_ALT = SARATHI_MFMA_ALTERNATE ? (N_S < N_O ? N_S : N_O) : 0;  // pairs (score, output) at the front
+    auto is_score = [&](int i) { return i < 2 * N_ALT ? (i & 1) == 0 : (SARATHI_MFMA_ALTERNATE ? N_S > N_O : i < N_S); };
+    auto sub_index = [&](int i) { return i < 2 * N_ALT ? (i >> 1) : i - N_ALT; };  // index within its kind
 
     // The step is laid out as NM slots fenced by scheduling barriers.  Slot i issues the LDS
     // read for MFMA i+AHEAD, then MFMA i, then its share of the vector-ALU work, which
     // executes while the matrix pipe is busy with MFMA i.
     auto operand = [&](int i) -> const uint16_t * {
-        if (i < N_S) return smem + K_OFF + k_chunk[i < NS ? i : 0];
-        const int j = i - N_S;  // output MFMA j: channel block j/2, page j%2
-        return smem + v_rd + (V_OFF + ((j & 1) * D + (j >> 1) * 32) * 16);
+        const int j = sub_index(i);
+        if (is_score(i)) return smem + K_OFF + k_chunk[j < NS ? j : 0];
+        // output MFMA j: page j / NB, channel block j % NB
+        return smem + v_rd + (V_OFF + ((j / NB) * D + (j % NB) * 32) * 16);
     };
     bf16x8 frag[AHEAD + 1];
 #pragma unroll
@@ -398,7 +412,8 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
         if (MASK_NEXT) s_next[r] = (next_key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? s_next[r] : -INFINITY;
         smax = fmaxf(smax, s_next[r]);
     };
-    constexpr int MAX_FROM = N_S + 2;  // first slot in which the finished scores may be touched
+    constexpr int LAST_SCORE = N_S == 0 ? -1 : (!SARATHI_MFMA_ALTERNATE ? N_S - 1 : (N_S <= N_O ? 2 * N_S - 2 : NM - 1));  // slot of the last score MFMA
+    constexpr int MAX_FROM = LAST_SCORE + 3;  // first slot in which the finished scores may be touched
     int w_done = 0, m_done = 0;         // compile-time after unrolling
     // Slot boundaries.  The arithmetic below has no side effects, so nothing but data flow
     // would keep it inside its slot; an empty asm that "touches" the values a slot produced and
@@ -412,18 +427,18 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
         bf16x8 &ahead = frag[(i + AHEAD) % (AHEAD + 1)];
         if (i + AHEAD < NM) ahead = lds_bf16x8(operand(i + AHEAD));
         const bf16x8 a = frag[i % (AHEAD + 1)];
-        if (i < N_S) {
-            if (i == 0) {
+        const int j = sub_index(i);
+        if (is_score(i)) {
+            if (j == 0) {
                 f32x16 zero;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) zero[r] = 0.f;
                 s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0], zero, 0, 0, 0);
             } else {
-                s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[i < NS ? i : 0], s_next, 0, 0, 0);
+                s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[j < NS ? j : 0], s_next, 0, 0, 0);
             }
         } else {
-            const int j = i - N_S;
-            st.oacc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, (j & 1) ? p_old1 : p_old0, st.oacc[j >> 1], 0, 0, 0);
+            st.oacc[j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, (j / NB) ? p_old1 : p_old0, st.oacc[j % NB], 0, 0, 0);
         }
         // vector-ALU share of this slot
         const int w_from = w_done;
@@ -439,11 +454,16 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
                 if (r >= m_done && r < m_target) next_max(r);
             m_done = m_target;
         }
-        // pin: this slot's MFMA result, the operand fetched ahead, the weights made here
-        if (i < N_S)
-            asm volatile("" : "+v"(s_next), "+v"(ahead), "+v"(neg_m), "+v"(psum), "+v"(e_even));
+        // pin: this slot's MFMA result and the weights made here.  The operand fetched ahead in
+        // this slot is NOT pinned (that would make the slot wait for it); the scheduling barrier
+        // alone keeps the read where it was issued.
+        bf16x8 &older = frag[i % (AHEAD + 1)];
+        if (is_score(i))
+            asm volatile("" : "+v"(s_next), "+v"(older), "+v"(neg_m), "+v"(psum), "+v"(e_even));
+        else if (i > LAST_SCORE)
+            asm volatile("" : "+v"(st.oacc[j % NB]), "+v"(older), "+v"(neg_m), "+v"(psum), "+v"(e_even), "+v"(s_next), "+v"(smax));
         else
-            asm volatile("" : "+v"(st.oacc[(i - N_S) >> 1]), "+v"(ahead), "+v"(neg_m), "+v"(psum), "+v"(e_even), "+v"(s_next), "+v"(smax));
+            asm volatile("" : "+v"(st.oacc[j % NB]), "+v"(older), "+v"(neg_m), "+v"(psum), "+v"(e_even));
 #pragma unroll
         for (int r = 1; r < 16; r += 2)
             if (r >= w_from && r < w_target) asm volatile("" : "+v"(p_new[r >> 1]));
@@ -531,16 +551,20 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
     const int n_tiles = tile_end - tile_begin;
     const int my_lds_base = (moves_v ? SM::kVBase : 0) + my_page * PAGE_ELEMS;
-    // this wave's page of tile `tile` -> ring slot (tile - tile_begin) % 4
-    auto issue_tile = [&](int tile) {
+    // page id of this wave's page of tile `tile` (a scalar load: issue it a step before it is needed)
+    auto page_of = [&](int tile) -> int64_t {
         int64_t pg = bt[min(tile * 2 + my_page, n_pages_seq - 1)];
-        pg = pg < 0 ? 0 : (pg > last_page_id ? last_page_id : pg);
+        return pg < 0 ? 0 : (pg > last_page_id ? last_page_id : pg);
+    };
+    // this wave's page `pg` of tile `tile` -> ring slot (tile - tile_begin) % 4
+    auto issue_page = [&](int tile, int64_t pg) {
         const uint16_t *src = cache_head + pg * page_stride;
         uint16_t *dst = smem + my_lds_base + ((tile - tile_begin) & (kRing - 1)) * TE;
 #pragma unroll
         for (int j = 0; j < LOADS_PER_PAGE; ++j)
             __builtin_amdgcn_global_load_lds((global_cptr)(src + g_off[j]), (lds_ptr)(dst + j * 512), 16, 0, 0);
     };
+    auto issue_tile = [&](int tile) { issue_page(tile, page_of(tile)); };
     const int my_ahead = moves_v ? 2 : 3;  // tiles this wave's loads run ahead of the step
 
     ChunkState<D> st;
@@ -582,16 +606,32 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         st.l_run = 0.f;  // the empty step contributed exp2(-inf) = 0 terms only
     }
 
+    int64_t pg_next = page_of(min(tile_begin + my_ahead, tile_end - 1));  // page id the first step will issue
     // Common head of a step for tile t, then the step proper.  Every loop below instantiates one
     // variant only, so its body stays a single basic block (plus the rare reference raise).
     auto step = [&](int tile, auto has_prev, auto has_next, auto mask_next) {
         // Tile t+1 must have landed (only this wave's loads of one later tile may still be in
         // flight), and every wave must be done with the slots about to be overwritten (K of
         // tile t-1, V of tile t-2).
+#ifdef SARATHI_TRACE
+        const bool tracer = blockIdx.x == 8 && tid == 0 && (tile - tile_begin) < 64;
+        uint32_t *trace = reinterpret_cast<uint32_t *>(p.part_o) + (tile - tile_begin) * 8;
+        if (tracer) trace[0] = (uint32_t)__builtin_amdgcn_s_memtime();
+#endif
         if (tile + my_ahead - 1 < tile_end) SARATHI_WAIT_VMCNT(LOADS_PER_PAGE); else SARATHI_WAIT_VMCNT(0);
+#ifdef SARATHI_TRACE
+        if (tracer) trace[1] = (uint32_t)__builtin_amdgcn_s_memtime();
+#endif
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (tile + my_ahead < tile_end) issue_tile(tile + my_ahead);
+#ifdef SARATHI_TRACE
+        if (tracer) trace[2] = (uint32_t)__builtin_amdgcn_s_memtime();
+#endif
+        if (tile + my_ahead < tile_end) issue_page(tile + my_ahead, pg_next);
+        pg_next = page_of(min(tile + my_ahead + 1, tile_end - 1));  // used by the next step
+#ifdef SARATHI_TRACE
+        if (tracer) trace[3] = (uint32_t)__builtin_amdgcn_s_memtime();
+#endif
         // raise the softmax reference if this tile exceeds it by more than the slack (rare)
         if (__any(st.tmax > st.m_ref + kRescaleSlack)) {
             const float m_new = fmaxf(st.m_ref, st.tmax);
@@ -603,9 +643,15 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         }
         const int rel = tile - tile_begin;
         const int next_key0 = (tile + 1) * kTileKeys + h * 8;
+#ifdef SARATHI_TRACE
+        if (tracer) trace[4] = (uint32_t)__builtin_amdgcn_s_memtime();
+#endif
         chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value>(
             st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE, ((rel + 3) & (kRing - 1)) * TE, scale,
             next_key0, pos_eff);
+#ifdef SARATHI_TRACE
+        if (tracer) trace[5] = (uint32_t)__builtin_amdgcn_s_memtime();
+#endif
     };
     using T = std::true_type;
     using F = std::false_type;
@@ -686,7 +732,10 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
 // loop has the registers it needs, the matrix pipe / vector ALU overlap comes from inside the wave.
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(AttnParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
+#ifndef SARATHI_CHUNK_LDS_PAD
+#define SARATHI_CHUNK_LDS_PAD 0
+#endif
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems + SARATHI_CHUNK_LDS_PAD];
     const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one unit
     const int blk = blockIdx.x / p.num_kv_heads;
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;

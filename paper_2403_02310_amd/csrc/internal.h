@@ -71,9 +71,9 @@ struct WorkspaceLayout {
 struct Options {
     int64_t split_keys = 0;         // 0 = automatic
     int64_t target_items = 1536;    // automatic choice aims for about this many wave units per KV head
-    int64_t tile_split_keys = 0;    // the same two knobs for the 128-column chunk tiles
-    int64_t tile_target_items = 96;
+    int64_t tile_split_keys = 0;    // keys per split of the 128-column chunk tiles, 0 = automatic
     int64_t tile_min_cols = 64;     // sequences with fewer columns (q_len*G) use wave tiles only
+    int64_t plan_at_append = 1;     // sarathi_kv_append also plans and uploads the attention metadata of its batch
     int64_t interleave = 1;         // run the chunk-tile kernel on a second stream next to the wave-tile kernel
 };
 

@@ -23,7 +23,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 constexpr int32_t kMaxSplitUnits = 8192;
 constexpr int32_t kMaxPartRows = 32768;
-constexpr int32_t kMinSplitKeys = 256;
+constexpr int32_t kMinSplitKeys = 512;
 constexpr int32_t kMinTileSplitKeys = 1024;
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
@@ -42,7 +42,7 @@ WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
     const size_t append_meta = sizeof(int32_t) * (2 * (size_t)cfg.max_seqs + (size_t)append_blocks(cfg, cfg.max_tokens)) + 64;
     size_t off = 0;
     w.meta = off;
-    w.meta_bytes = align_up(std::max(attn_meta, append_meta), 256);
+    w.meta_bytes = align_up(align_up(append_meta, 256) + attn_meta, 256);  // an append may carry both
     off += w.meta_bytes;
     w.part_ml = off;   off = align_up(off + sizeof(float) * 2 * (size_t)w.max_part_rows * cfg.num_kv_heads, 256);
     w.part_o = off;    off = align_up(off + sizeof(float) * (size_t)w.max_part_rows * cfg.num_kv_heads * cfg.head_dim, 256);
@@ -191,7 +191,10 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         return ceil_div(k, kTileKeys) * kTileKeys;
     };
     int64_t wave_split = pick(opt.split_keys, keys_of_kind[kKindWave], opt.target_items, kMinSplitKeys);
-    int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], opt.tile_target_items, kMinTileSplitKeys);
+    // Chunk tiles: enough units per KV head to put two blocks on every compute unit (a block
+    // alone on its unit cannot hide its per-step latencies), but never pieces below the floor.
+    const int64_t tile_units_wanted = std::max<int64_t>(1, 768 / cfg.num_kv_heads);
+    int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], tile_units_wanted, kMinTileSplitKeys);
     for (;;) {
         int64_t n_split_units = 0, rows = 0, n_split_tiles = 0;
         count_splits(plan, 0, n_chunk_tiles, tile_split, n_split_units, rows, n_split_tiles);
