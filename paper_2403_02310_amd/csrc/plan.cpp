@@ -190,11 +190,17 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         int64_t k = forced > 0 ? forced : std::max<int64_t>(floor_keys, ceil_div(total, std::max<int64_t>(1, target)));
         return ceil_div(k, kTileKeys) * kTileKeys;
     };
-    int64_t wave_split = pick(opt.split_keys, keys_of_kind[kKindWave], opt.target_items, kMinSplitKeys);
+    // Wave tiles that share the chip with chunk tiles are cut finer: the two kernels compete for
+    // block slots and shorter units interleave better (measured on the Mistral-shape hybrid batch).
+    const int64_t wave_floor = n_chunk_tiles > 0 ? kMinSplitKeys / 2 : kMinSplitKeys;
+    int64_t wave_split = pick(opt.split_keys, keys_of_kind[kKindWave], opt.target_items, wave_floor);
     // Chunk tiles: enough units per KV head to put two blocks on every compute unit (a block
     // alone on its unit cannot hide its per-step latencies), but never pieces below the floor.
+    // Next to wave tiles the floor is higher: the chunk kernel then runs in the shadow of the
+    // memory-bound one and every split avoided saves partial rows that need merging.
     const int64_t tile_units_wanted = std::max<int64_t>(1, 768 / cfg.num_kv_heads);
-    int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], tile_units_wanted, kMinTileSplitKeys);
+    const int64_t tile_floor = plan.tiles.size() > n_chunk_tiles ? 2 * kMinTileSplitKeys : kMinTileSplitKeys;
+    int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], tile_units_wanted, tile_floor);
     for (;;) {
         int64_t n_split_units = 0, rows = 0, n_split_tiles = 0;
         count_splits(plan, 0, n_chunk_tiles, tile_split, n_split_units, rows, n_split_tiles);
