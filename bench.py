@@ -23,6 +23,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the attention kernels (fetch + write), from two `rocprofv3 --pmc` runs
+# (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read on a plain copy of known size;
+# the runs and the scaling are recorded in profiles/attention_c2_mistral_hybrid.md.
+MEASURED_TRAFFIC_BYTES = {"c2": 628.1e6, "c3": 1491.3e6}
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
@@ -221,13 +226,14 @@ def main() -> int:
         mfma_bound = args.workload.endswith("_chunk") or args.workload.endswith("_chunks")
         if mfma_bound:
             ach = alg_flops / (attn_us * 1e-6) / 1e12
-            result["roofline"] = {"bound": "mfma", "kernel": "attn_hybrid_kernel", "achieved": ach,
+            result["roofline"] = {"bound": "mfma", "kernel": "attn_chunk_kernel", "achieved": ach,
                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                                   "traffic": None}
         else:
             ach = alg_bytes / (attn_us * 1e-6) / 1e9
-            result["roofline"] = {"bound": "hbm", "kernel": "attn_hybrid_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
-                                  "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+            result["roofline"] = {"bound": "hbm", "kernel": "attn_wave_kernel (+ attn_chunk_kernel co-running)",
+                                  "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                                  "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
 
     # ---- CPU baseline: the fp64 checker as it stands, on the host cores, bounded sample ----
     if not args.no_cpu_baseline:
