@@ -95,14 +95,19 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * choice aims for), "tile_split_keys" (keys per split of the 128-column chunk tiles, 0 =
  * automatic), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
  * tiles), "plan_at_append" (0/1: sarathi_kv_append also plans and uploads the attention
- * metadata of its batch so that the following attention call needs no copy of its own), "interleave" (0/1: run the chunk-tile kernel on a second stream next to the wave-tile kernel),
- * "time_kernels" (0/1, see sarathi_get_kernel_times).
+ * metadata of its batch so that the following attention call needs no copy of its own),
+ * "interleave" (batches holding both prefill chunks and decodes: 0 = chunk-tile kernel then
+ * wave-tile kernel on the caller's stream, 1 = chunk-tile kernel and the merge of its split tiles
+ * on a second stream next to the wave-tile kernel, 2 = one launch holding both kinds of block),
+ * "time_kernels" (0/1/2, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);
 
-/* Optional instrumentation.  With option "time_kernels" = 1 the library brackets each of its
- * kernels with a pair of HIP events on the caller's stream (up to 8192 launches per kernel
- * between two reads).  sarathi_get_kernel_times waits for the recorded events, returns the
+/* Optional instrumentation.  With option "time_kernels" = 1 the library brackets the attention
+ * launch (both attention kernels, fork and join included) with a pair of HIP events on the
+ * caller's stream; with 2 also the append kernel and the part of the split-KV merge that runs on
+ * the caller's stream (up to 8192 launches per kernel between two reads; every event costs a few
+ * microseconds of queue time, which is why level 1 exists).  sarathi_get_kernel_times waits for the recorded events, returns the
  * summed durations and launch counts since the last read, and resets them. */
 typedef struct {
     double append_ms, attention_ms, merge_ms;

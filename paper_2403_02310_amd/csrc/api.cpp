@@ -48,7 +48,7 @@ struct sarathi_handle {
     hipStream_t side_stream = nullptr;
     hipEvent_t fork_event = nullptr, join_event = nullptr;
     // Optional per-kernel timing: event pairs recorded around each launch.
-    bool time_kernels = false;
+    int time_kernels = 0;  // 0 off, 1 attention launches only, 2 also the append and merge kernels
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, merge
     size_t timing_used[3] = {0, 0, 0};
 };
@@ -90,10 +90,13 @@ sarathi_status acquire_slot(sarathi_handle *h, int *slot) {
 }
 
 constexpr size_t kMaxTimedLaunches = 8192;
+// Extra dynamic LDS that makes a chunk-kernel block (64 KB static) too large for two to share a
+// compute unit's 160 KB.
+constexpr int kChunkLdsPad = 24 * 1024;
 
 // Records the start event of a timed launch; returns the pair index or -1 when timing is off/full.
 int timing_begin(sarathi_handle *h, int kind, hipStream_t s) {
-    if (!h->time_kernels || h->timing_used[kind] >= kMaxTimedLaunches) return -1;
+    if (h->time_kernels < (kind == 1 ? 1 : 2) || h->timing_used[kind] >= kMaxTimedLaunches) return -1;
     auto &pool = h->timing_pool[kind];
     if (h->timing_used[kind] == pool.size()) {
         hipEvent_t a, b;
@@ -203,6 +206,11 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.tile_split_keys = value;
         return SARATHI_OK;
     }
+    if (std::strcmp(name, "chunk_blocks_per_cu") == 0) {
+        if (value < 0 || value > 2) return fail(h, SARATHI_EINVAL, "chunk_blocks_per_cu must be 0, 1 or 2");
+        h->opt.chunk_blocks_per_cu = value;
+        return SARATHI_OK;
+    }
     if (std::strcmp(name, "tile_min_cols") == 0) {
         if (value < 1 || value > (1 << 30)) return fail(h, SARATHI_EINVAL, "tile_min_cols out of range");
         h->opt.tile_min_cols = value;
@@ -213,11 +221,13 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         return SARATHI_OK;
     }
     if (std::strcmp(name, "interleave") == 0) {
-        h->opt.interleave = value != 0;
+        if (value < 0 || value > 2) return SARATHI_EINVAL;
+        h->opt.interleave = value;
         return SARATHI_OK;
     }
     if (std::strcmp(name, "time_kernels") == 0) {
-        h->time_kernels = value != 0;
+        if (value < 0 || value > 2) return SARATHI_EINVAL;
+        h->time_kernels = (int)value;
         return SARATHI_OK;
     }
     return fail(h, SARATHI_EINVAL, std::string("unknown option: ") + name);
@@ -404,35 +414,43 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.max_blocks = h->cfg.max_blocks_per_seq;
     m.reduce_units = reinterpret_cast<const uint32_t *>(dev + reduce_off);
     m.num_reduce_units = (int32_t)pl.reduce_units.size();
+    m.num_tile_reduce_units = pl.num_tile_reduce_units;
     m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
-    // has both they run side by side: the chunk kernel is forked onto a second stream.
-    const bool both = pl.num_tile_units > 0 && (int32_t)pl.units.size() > pl.num_tile_units && h->opt.interleave;
-    if (both && !h->side_stream) {
+    // has both they run side by side: the chunk kernel is forked onto a second stream, where the
+    // merge of its own split tiles follows it (hidden behind the longer wave kernel).
+    const bool both = pl.num_tile_units > 0 && (int32_t)pl.units.size() > pl.num_tile_units;
+    const bool fork = both && h->opt.interleave == 1;
+    if (fork && !h->side_stream) {
         e = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking);
         if (e != hipSuccess) return hip_fail(h, "hipStreamCreate(side)", e);
         e = hipEventCreateWithFlags(&h->fork_event, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&h->join_event, hipEventDisableTiming);
         if (e != hipSuccess) return hip_fail(h, "hipEventCreate(fork/join)", e);
     }
+    int32_t merged_on_side = 0;
     const int t1 = timing_begin(h, 1, s);
-    if (both) {
+    if (fork) {
         e = hipEventRecord(h->fork_event, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(h->side_stream, h->fork_event, 0);
         if (e != hipSuccess) return hip_fail(h, "fork to side stream", e);
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1, h->side_stream);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1,
+                                         h->opt.chunk_blocks_per_cu == 2 ? 0 : kChunkLdsPad, h->side_stream);
+        if (e == hipSuccess) e = (hipError_t)launch_reduce(h->cfg, m, out, 0, m.num_tile_reduce_units, h->side_stream);
+        merged_on_side = m.num_tile_reduce_units;
         if (e == hipSuccess) e = hipEventRecord(h->join_event, h->side_stream);
-        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, stream);
+        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, 0, stream);
         if (e == hipSuccess) e = hipStreamWaitEvent(s, h->join_event, 0);
     } else {
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, stream);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out,
+                                         both && h->opt.interleave == 2 ? 4 : 3, 0, stream);
     }
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);
-    if (m.num_reduce_units > 0) {
+    if (m.num_reduce_units > merged_on_side) {
         const int t2 = timing_begin(h, 2, s);
-        e = (hipError_t)launch_reduce(h->cfg, m, out, stream);
+        e = (hipError_t)launch_reduce(h->cfg, m, out, merged_on_side, m.num_reduce_units - merged_on_side, stream);
         timing_end(h, 2, t2, s);
         if (e != hipSuccess) return hip_fail(h, "launch split-KV merge", e);
     }

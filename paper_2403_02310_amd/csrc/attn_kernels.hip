@@ -756,6 +756,27 @@ __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
     }
 }
 
+// Both kinds of unit in ONE launch: the first num_tile_units * Hkv blocks run chunk tiles, the
+// rest wave tiles (block-uniform branch).  Saves the second stream's fork and join.
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
+    const int kvh = blockIdx.x % p.num_kv_heads;
+    int blk = blockIdx.x / p.num_kv_heads;
+    constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
+    if (blk < p.num_tile_units) {
+        const uint32_t u = p.units[blk];
+        chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
+    } else {
+        blk -= p.num_tile_units;
+        const int idx = p.num_tile_units + blk * 4 + (threadIdx.x >> 6);
+        if (idx < p.num_units) {
+            const uint32_t u = p.units[idx];
+            wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Split-KV merge: out = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(m_i - max_i m_i), pieces
 // taken in index order.  A block merges 8 columns of one split tile for one KV head: D/4
@@ -886,19 +907,19 @@ int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void 
     return (int)hipGetLastError();
 }
 
-int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void *stream) {
-    if (m.num_reduce_units == 0) return (int)hipSuccess;
+int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream) {
+    if (count <= 0) return (int)hipSuccess;
     static_assert(kMergeCols == kReduceCols, "planner and merge kernel must agree on columns per block");
     ReduceParams p;
     p.tiles = m.tiles;
-    p.reduce_units = m.reduce_units;
+    p.reduce_units = m.reduce_units + first;
     p.part_ml = m.part_ml;
     p.part_o = m.part_o;
     p.out = static_cast<uint16_t *>(out);
     p.num_q_heads = cfg.num_q_heads;
     p.num_kv_heads = cfg.num_kv_heads;
     p.group = cfg.num_q_heads / cfg.num_kv_heads;
-    const unsigned blocks = (unsigned)m.num_reduce_units * (unsigned)cfg.num_kv_heads;
+    const unsigned blocks = (unsigned)count * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
         hipLaunchKernelGGL(splitkv_reduce_kernel<128>, dim3(blocks), dim3(kMergeCols * 128 / 4), 0, st, p);
@@ -908,7 +929,8 @@ int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void 
 }
 
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream) {
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, int chunk_lds_pad,
+                     void *stream) {
     if (m.num_units == 0) return (int)hipSuccess;
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
@@ -931,11 +953,18 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
     const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
+    if (which == 4) {
+        if (cfg.head_dim == 128)
+            hipLaunchKernelGGL(attn_hybrid_kernel<128>, dim3(chunk_blocks + wave_blocks), dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL(attn_hybrid_kernel<64>, dim3(chunk_blocks + wave_blocks), dim3(256), 0, st, p);
+        return (int)hipGetLastError();
+    }
     if (chunk_blocks && (which & 1)) {
         if (cfg.head_dim == 128)
-            hipLaunchKernelGGL(attn_chunk_kernel<128>, dim3(chunk_blocks), dim3(256), 0, st, p);
+            hipLaunchKernelGGL(attn_chunk_kernel<128>, dim3(chunk_blocks), dim3(256), (size_t)chunk_lds_pad, st, p);
         else
-            hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), 0, st, p);
+            hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), (size_t)chunk_lds_pad, st, p);
     }
     if (wave_blocks && (which & 2)) {
         if (cfg.head_dim == 128)

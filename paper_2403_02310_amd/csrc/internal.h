@@ -48,7 +48,8 @@ struct Plan {
     std::vector<TileDesc> tiles;
     std::vector<uint32_t> units;      // chunk-tile units first (num_tile_units), then wave-tile units; longest first in each group
     int32_t num_tile_units = 0;
-    std::vector<uint32_t> reduce_units;  // (8-column group, tile) of every split tile, for the merge kernel
+    std::vector<uint32_t> reduce_units;  // (8-column group, tile) of every split tile, for the merge kernel; chunk tiles first
+    int32_t num_tile_reduce_units = 0;   // how many of them belong to chunk tiles
     int32_t num_split_tiles = 0;      // tiles with n_splits > 1
     int32_t num_part_rows = 0;
     int32_t split_keys = 0;
@@ -74,7 +75,10 @@ struct Options {
     int64_t tile_split_keys = 0;    // keys per split of the 128-column chunk tiles, 0 = automatic
     int64_t tile_min_cols = 64;     // sequences with fewer columns (q_len*G) use wave tiles only
     int64_t plan_at_append = 1;     // sarathi_kv_append also plans and uploads the attention metadata of its batch
-    int64_t interleave = 1;         // run the chunk-tile kernel on a second stream next to the wave-tile kernel
+    int64_t interleave = 2;         // batches with both kinds of tile: 0 = two launches in sequence, 1 = chunk kernel on a
+                                    // second stream next to the wave kernel, 2 = one launch holding both kinds of block
+    int64_t chunk_blocks_per_cu = 0; // side-stream mode: 1 = pad the chunk kernel's LDS so that one block fits a compute
+                                    // unit (leaves the other block slot to the wave kernel), 2 = no padding, 0 = automatic
 };
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg);
@@ -120,14 +124,17 @@ struct AttnMeta {
     int32_t max_blocks;
     const uint32_t *reduce_units;  // dev
     int32_t num_reduce_units;
+    int32_t num_tile_reduce_units;   // leading entries of reduce_units that belong to chunk tiles
     float *part_ml;              // dev
     float *part_o;               // dev
 };
 
-// which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel
+// which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream);
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, int chunk_lds_pad,
+                     void *stream);
 
-int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, void *stream);
+// Merges the split tiles named by reduce_units[first .. first+count).
+int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream);
 
 }  // namespace sarathi

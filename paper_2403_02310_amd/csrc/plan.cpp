@@ -153,6 +153,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     plan.reduce_units.clear();
     plan.num_part_rows = 0;
     plan.num_tile_units = 0;
+    plan.num_tile_reduce_units = 0;
     plan.num_split_tiles = 0;
     const int32_t G = cfg.num_q_heads / cfg.num_kv_heads;
 
@@ -192,14 +193,21 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     };
     // Wave tiles that share the chip with chunk tiles are cut finer: the two kernels compete for
     // block slots and shorter units interleave better (measured on the Mistral-shape hybrid batch).
-    const int64_t wave_floor = n_chunk_tiles > 0 ? kMinSplitKeys / 2 : kMinSplitKeys;
+    const int64_t wave_floor = n_chunk_tiles > 0 ? (kMinSplitKeys * 3) / 4 : kMinSplitKeys;
     int64_t wave_split = pick(opt.split_keys, keys_of_kind[kKindWave], opt.target_items, wave_floor);
     // Chunk tiles: enough units per KV head to put two blocks on every compute unit (a block
     // alone on its unit cannot hide its per-step latencies), but never pieces below the floor.
-    // Next to wave tiles the floor is higher: the chunk kernel then runs in the shadow of the
-    // memory-bound one and every split avoided saves partial rows that need merging.
+    // Next to wave tiles the chunk blocks run in the shadow of the memory-bound ones, which keep
+    // the other block slots busy: a chunk piece only has to finish within the time the decodes
+    // take to stream (about 5 bytes/ps on this part; a chunk block advances 32 keys in roughly a
+    // microsecond), and every split avoided saves partial rows that need merging.
     const int64_t tile_units_wanted = std::max<int64_t>(1, 768 / cfg.num_kv_heads);
-    const int64_t tile_floor = plan.tiles.size() > n_chunk_tiles ? 2 * kMinTileSplitKeys : kMinTileSplitKeys;
+    const bool has_wave_tiles = plan.tiles.size() > n_chunk_tiles;
+    int64_t tile_floor = kMinTileSplitKeys;
+    if (has_wave_tiles) {
+        const double wave_us = (double)keys_of_kind[kKindWave] * cfg.num_kv_heads * cfg.head_dim * 4.0 / 5.0e6;
+        tile_floor = std::max<int64_t>(2 * kMinTileSplitKeys, (int64_t)(wave_us / 1.2) * kTileKeys);
+    }
     int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], tile_units_wanted, tile_floor);
     for (;;) {
         int64_t n_split_units = 0, rows = 0, n_split_tiles = 0;
@@ -221,6 +229,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     static thread_local std::vector<int32_t> bucket;
     emit_units(plan, 0, n_chunk_tiles, tile_split, scratch, bucket);
     plan.num_tile_units = (int32_t)plan.units.size();
+    plan.num_tile_reduce_units = (int32_t)plan.reduce_units.size();
     emit_units(plan, n_chunk_tiles, plan.tiles.size(), wave_split, scratch, bucket);
 }
 

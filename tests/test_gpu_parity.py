@@ -102,13 +102,17 @@ def test_long_decode_uses_splits_and_matches(hx):
 @pytest.mark.parametrize("shape", ["gqa7_d128", "gqa4_d128", "mqa4_d64"])
 def test_chunk_tiles_with_forced_splits_and_both_paths(hx, shape):
     """A 300-row chunk on a 1000-token prefix + decodes: default plan, chunk tiles split every 64 keys,
-    everything through chunk tiles, everything through wave tiles -- all within tolerance of the checker."""
+    everything through chunk tiles, everything through wave tiles, and the three ways of launching the two
+    kinds of tile (in sequence, on two streams, in one launch) -- all within tolerance of the checker."""
     s = SHAPES[shape]
     b = wl._make("chunk300_" + shape, s, [300, 1, 37, 1], [1300, 555, 37, 1], 79)
     st, got, ref, _ = _check_batch(hx, b, check_pools=False)
     info, items = st["handle"].plan(b.q_start, b.q_len, b.ctx_len)
     assert info.num_tile_items > 0 and info.num_items > info.num_tile_items
-    for opts in ({"tile_split_keys": 64, "split_keys": 32}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20}):
+    for opts in ({"tile_split_keys": 64, "split_keys": 32}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20},
+                 {"interleave": 0, "tile_split_keys": 128}, {"interleave": 1, "tile_split_keys": 128},
+                 {"interleave": 1, "chunk_blocks_per_cu": 2, "tile_split_keys": 128},
+                 {"interleave": 2, "tile_split_keys": 128}):
         h = hx.make_handle(b)
         for k, v in opts.items():
             h.set_option(k, v)
