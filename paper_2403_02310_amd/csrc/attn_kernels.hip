@@ -327,8 +327,24 @@ __device__ __forceinline__ bf16x8 lds_bf16x8(const uint16_t *p) {
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
 }
 
-typedef const void __attribute__((address_space(1))) *global_cptr;
 typedef void __attribute__((address_space(3))) *lds_ptr;
+
+// One direct global -> LDS load of 16 bytes per lane (1 KiB per wavefront): lane l fetches
+// base + byte_off(l) and the wavefront's data lands at LDS byte address lds_addr + 16 l.
+// Written as inline assembly on purpose: the compiler's wait-count bookkeeping treats the
+// builtin form as a flat access that may return out of order with LDS reads, and from then on
+// turns every wait for an LDS operand into a full drain of the LDS queue (one pipeline bubble
+// per four MFMAs in the loop below).  The loads issued here are waited for by hand
+// (SARATHI_WAIT_VMCNT), the only vector-memory accesses of the chunk loop.
+__device__ __forceinline__ void dma_load_16(const uint16_t *base, int byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(byte_off), "s"(base)
+                 : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const uint16_t *p) {
+    return (uint32_t)(uintptr_t)(lds_ptr)(p);
+}
 typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
@@ -339,9 +355,11 @@ typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
 template <int D>
 struct ChunkState {
     f32x16 oacc[D / 32];  // O^T accumulators: channel 32c + 8*(r/4) + 4h + r%4, column n
-    f32x16 s_cur;         // raw scores of the tile whose softmax is due (already masked)
-    bf16x8 p_prev[2];     // bf16 softmax weights of the previous tile (B operands of its output MFMAs)
-    float tmax;           // scaled maximum of s_cur over the column
+    // Two register sets used in turn by consecutive steps of the unrolled loop (a step reads one
+    // and fills the other); steps outside that loop keep everything in set 0.
+    f32x16 s[2];          // raw scores of the tile whose softmax is due (already masked)
+    bf16x8 p[2][2];       // bf16 softmax weights of the previous tile (B operands of its output MFMAs)
+    float tmax;           // scaled maximum of the due scores over the column
     float m_ref;          // softmax reference, scaled base-2 units
     float l_run;          // this lane's share of the running sum
 };
@@ -352,10 +370,48 @@ struct ChunkState {
 //   VALU:  P(t) = 2^(S(t)*scale - m_ref), row sums, bf16 packing; mask and maximum of S(t+1)
 // k_chunk: this lane's (swizzled) K chunk offsets; K_OFF / V_OFF: element offsets of the ring
 // slots read in this step (wave-uniform).
-template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT>
+// Order of the MFMAs of a step: which kind slot i issues and its index within that kind.
+// Scores come in pairs with an output MFMA between the pairs ("S S O S S O ...") while both kinds
+// last: the scores are then complete a few slots before the end of the step, so that masking and
+// the maximum of the next tile also run under MFMAs, and the output MFMAs that close the step use
+// four different accumulators in turn.
+struct ChunkSlot {
+    bool is_score;
+    int sub;
+};
+#ifndef SARATHI_MFMA_ORDER
+#define SARATHI_MFMA_ORDER 1
+#endif
+constexpr ChunkSlot chunk_slot(int i, int n_s, int n_o) {
+    int sc = 0, ou = 0;
+    for (int k = 0;; ++k) {
+        bool pick_s = false;
+        if (sc >= n_s) pick_s = false;
+        else if (ou >= n_o) pick_s = true;
+        else pick_s = SARATHI_MFMA_ORDER == 0 ? (k % 2 == 0) : (k % 3 != 2);
+        if (k == i) return ChunkSlot{pick_s, pick_s ? sc : ou};
+        if (pick_s) ++sc; else ++ou;
+    }
+}
+constexpr int chunk_last_score_slot(int n_s, int n_o) {
+    int last = -1;
+    for (int i = 0; i < n_s + n_o; ++i)
+        if (chunk_slot(i, n_s, n_o).is_score) last = i;
+    return last;
+}
+
+// PHASE >= 0: the tile's index inside the unit is PHASE modulo 4, which fixes the ring slots at
+// compile time (K_OFF_RT / V_OFF_RT are ignored and the operand reads need no address
+// arithmetic); PHASE < 0: slots given at run time.  The step reads register set PP and fills set
+// PP ^ 1 (SWAP) or set PP again (the results are copied back).
+template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT, int PHASE = -1, int PP = 0, bool SWAP = false>
 __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qreg)[D / 16], const uint16_t *smem,
-                                           const int (&k_chunk)[D / 16], int v_rd, int K_OFF, int V_OFF, float scale,
+                                           const int (&k_chunk)[D / 16], int v_rd, int K_OFF_RT, int V_OFF_RT, float scale,
                                            int next_key0, int pos_eff) {
+    constexpr int TE_ = kTileKeys * D;
+    const int K_OFF = PHASE >= 0 ? ((PHASE + 1) & (kRing - 1)) * TE_ : K_OFF_RT;
+    const int V_OFF = PHASE >= 0 ? ((PHASE + 3) & (kRing - 1)) * TE_ : V_OFF_RT;
+    constexpr int OUT = SWAP ? (PP ^ 1) : PP;
     constexpr int NS = D / 16;
     constexpr int NB = D / 32;
     constexpr int N_S = HAS_NEXT ? NS : 0;              // score MFMAs (one dependent chain through s_next)
@@ -365,15 +421,8 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
 #define SARATHI_AHEAD 3
 #endif
     constexpr int AHEAD = SARATHI_AHEAD;                 // operand reads run this many MFMAs ahead
-    // MFMA order: score and output MFMAs alternate while both kinds last, so that an MFMA never
-    // follows the one whose accumulator it needs (the score chain is dependent, and so are the
-    // two pages of one output block); the output MFMAs go page-major for the same reason.
-#ifndef SARATHI_MFMA_ALTERNATE
-#define SARATHI_MFMA_ALTERNATE 1
-#endif
-    constexpr int N_ALT = SARATHI_MFMA_ALTERNATE ? (N_S < N_O ? N_S : N_O) : 0;  // pairs (score, output) at the front
-    auto is_score = [&](int i) { return i < 2 * N_ALT ? (i & 1) == 0 : (SARATHI_MFMA_ALTERNATE ? N_S > N_O : i < N_S); };
-    auto sub_index = [&](int i) { return i < 2 * N_ALT ? (i >> 1) : i - N_ALT; };  // index within its kind
+    auto is_score = [&](int i) { return chunk_slot(i, N_S, N_O).is_score; };
+    auto sub_index = [&](int i) { return chunk_slot(i, N_S, N_O).sub; };
 
     // The step is laid out as NM slots fenced by scheduling barriers.  Slot i issues the LDS
     // read for MFMA i+AHEAD, then MFMA i, then its share of the vector-ALU work, which
@@ -388,8 +437,10 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
 #pragma unroll
     for (int i = 0; i < AHEAD && i < NM; ++i) frag[i] = lds_bf16x8(operand(i));
 
-    f32x16 s_next;
-    const bf16x8 p_old0 = st.p_prev[0], p_old1 = st.p_prev[1];
+    f32x16 s_tmp;
+    f32x16 &s_next = SWAP ? st.s[OUT] : s_tmp;
+    const f32x16 &s_cur = st.s[PP];
+    const bf16x8 p_old0 = st.p[PP][0], p_old1 = st.p[PP][1];
     typedef __attribute__((ext_vector_type(2))) float f32x2;
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     uint32_t p_new[8];  // bf16 pairs of the current tile's weights: registers (2k, 2k+1)
@@ -398,7 +449,7 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
     float smax = -INFINITY;
     float neg_m = -st.m_ref;
     auto weight = [&](int r) {
-        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s_cur[r], scale, neg_m));
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[r], scale, neg_m));
         psum += e;
         if (r & 1) {
             const bf16x2 pk = __builtin_convertvector(f32x2{e_even, e}, bf16x2);
@@ -412,8 +463,8 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
         if (MASK_NEXT) s_next[r] = (next_key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? s_next[r] : -INFINITY;
         smax = fmaxf(smax, s_next[r]);
     };
-    constexpr int LAST_SCORE = N_S == 0 ? -1 : (!SARATHI_MFMA_ALTERNATE ? N_S - 1 : (N_S <= N_O ? 2 * N_S - 2 : NM - 1));  // slot of the last score MFMA
-    constexpr int MAX_FROM = LAST_SCORE + 3;  // first slot in which the finished scores may be touched
+    constexpr int LAST_SCORE = chunk_last_score_slot(N_S, N_O);  // slot of the last score MFMA
+    constexpr int MAX_FROM = LAST_SCORE + 2;  // first slot in which the finished scores may be touched
     int w_done = 0, m_done = 0;         // compile-time after unrolling
     // Slot boundaries.  The arithmetic below has no side effects, so nothing but data flow
     // would keep it inside its slot; an empty asm that "touches" the values a slot produced and
@@ -477,14 +528,17 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             if (r >= m_done) next_max(r);
-        smax = fmaxf(smax, __shfl_xor(smax, 32));
+        // the other half-wave holds the other 16 keys of the column: one VALU half-swap, no LDS trip
+        const auto halves = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, smax),
+                                                             __builtin_bit_cast(uint32_t, smax), false, false);
+        smax = fmaxf(__builtin_bit_cast(float, (uint32_t)halves[0]), __builtin_bit_cast(float, (uint32_t)halves[1]));
         st.tmax = smax * scale;  // scale > 0
-        st.s_cur = s_next;
+        if (!SWAP) st.s[OUT] = s_tmp;
     }
     st.l_run += psum;
     typedef __attribute__((ext_vector_type(4))) uint32_t pk4;
-    st.p_prev[0] = __builtin_bit_cast(bf16x8, pk4{p_new[0], p_new[1], p_new[2], p_new[3]});
-    st.p_prev[1] = __builtin_bit_cast(bf16x8, pk4{p_new[4], p_new[5], p_new[6], p_new[7]});
+    st.p[OUT][0] = __builtin_bit_cast(bf16x8, pk4{p_new[0], p_new[1], p_new[2], p_new[3]});
+    st.p[OUT][1] = __builtin_bit_cast(bf16x8, pk4{p_new[4], p_new[5], p_new[6], p_new[7]});
 }
 
 template <int D>
@@ -497,6 +551,12 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     constexpr int LOADS_PER_PAGE = PAGE_ELEMS / 512;  // 1 KiB wavefront loads per page of one KV head
     using SM = ChunkSmem<D>;
     constexpr int TE = SM::kTileElems;
+#ifndef SARATHI_CHUNK_PRIO
+#define SARATHI_CHUNK_PRIO 3
+#endif
+    // Chunk waves are latency-bound chains of dependent steps; the decode waves they may share a
+    // SIMD with are memory-bound and have issue slots to spare.  Issue priority goes to the chunk.
+    __builtin_amdgcn_s_setprio(SARATHI_CHUNK_PRIO);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; tell the compiler
@@ -532,7 +592,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     // K pages run three tiles ahead of the step, V pages two (V is consumed two steps later than K).
     const bool moves_v = wave >= 2;
     const int my_page = wave & 1;
-    int g_off[LOADS_PER_PAGE];  // element offset inside the page of one KV head
+    int g_off[LOADS_PER_PAGE];  // this lane's byte offset inside the page of one KV head, per load
 #pragma unroll
     for (int j = 0; j < LOADS_PER_PAGE; ++j) {
         const int q = j * 64 + lane;
@@ -540,7 +600,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         const int k_elem = k_slot * D + ((q % CPR) ^ k_swizzle<D>(k_slot)) * 8;
         const int v_d = q >> 1;
         const int v_elem = (v_d * 2 + ((q & 1) ^ ((v_d >> 3) & 1))) * 8;
-        g_off[j] = moves_v ? v_elem : k_elem;
+        g_off[j] = (moves_v ? v_elem : k_elem) * 2;
     }
     const const_i32_ptr bt = (const_i32_ptr)(p.block_table + (int64_t)seq * p.max_blocks);  // read-only: scalar loads
     const int n_pages_seq = (ctx + kPageSize - 1) / kPageSize;
@@ -551,18 +611,23 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
     const int n_tiles = tile_end - tile_begin;
     const int my_lds_base = (moves_v ? SM::kVBase : 0) + my_page * PAGE_ELEMS;
+    const uint32_t smem_addr = lds_address(smem);
     // page id of this wave's page of tile `tile` (a scalar load: issue it a step before it is needed)
-    auto page_of = [&](int tile) -> int64_t {
-        int64_t pg = bt[min(tile * 2 + my_page, n_pages_seq - 1)];
+    // The raw table entry and its clamp are separate so that the entry can be fetched a step
+    // before it is needed and only then looked at (the clamp would otherwise wait for the load).
+    auto page_raw = [&](int tile) -> int32_t { return bt[min(tile * 2 + my_page, n_pages_seq - 1)]; };
+    auto page_clamp = [&](int32_t raw) -> int64_t {
+        const int64_t pg = raw;
         return pg < 0 ? 0 : (pg > last_page_id ? last_page_id : pg);
     };
+    auto page_of = [&](int tile) -> int64_t { return page_clamp(page_raw(tile)); };
     // this wave's page `pg` of tile `tile` -> ring slot (tile - tile_begin) % 4
     auto issue_page = [&](int tile, int64_t pg) {
         const uint16_t *src = cache_head + pg * page_stride;
-        uint16_t *dst = smem + my_lds_base + ((tile - tile_begin) & (kRing - 1)) * TE;
+        const uint32_t dst = smem_addr + (uint32_t)(my_lds_base + ((tile - tile_begin) & (kRing - 1)) * TE) * 2;
 #pragma unroll
         for (int j = 0; j < LOADS_PER_PAGE; ++j)
-            __builtin_amdgcn_global_load_lds((global_cptr)(src + g_off[j]), (lds_ptr)(dst + j * 512), 16, 0, 0);
+            dma_load_16(src, g_off[j], dst + j * 1024);
     };
     auto issue_tile = [&](int tile) { issue_page(tile, page_of(tile)); };
     const int my_ahead = moves_v ? 2 : 3;  // tiles this wave's loads run ahead of the step
@@ -596,8 +661,8 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     asm volatile("" ::: "memory");
     {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st.s_cur[r] = -INFINITY;  // "current" tile of the empty step: weights 0
-        st.p_prev[0] = st.p_prev[1] = bf16x8{};
+        for (int r = 0; r < 16; ++r) st.s[0][r] = -INFINITY;  // "current" tile of the empty step: weights 0
+        st.p[0][0] = st.p[0][1] = bf16x8{};
         const int key0 = tile_begin * kTileKeys + h * 8;
         if (tile_begin >= mask_from)
             chunk_step<D, false, true, true>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
@@ -606,19 +671,22 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         st.l_run = 0.f;  // the empty step contributed exp2(-inf) = 0 terms only
     }
 
-    int64_t pg_next = page_of(min(tile_begin + my_ahead, tile_end - 1));  // page id the first step will issue
+    int32_t pg_next = page_raw(tile_begin + my_ahead);  // table entry of the page the first step will fetch
     // Common head of a step for tile t, then the step proper.  Every loop below instantiates one
     // variant only, so its body stays a single basic block (plus the rare reference raise).
-    auto step = [&](int tile, auto has_prev, auto has_next, auto mask_next) {
+    // Every step but a unit's last fetches this wave's page of tile t + my_ahead; beyond the
+    // unit's end that is a clamped, unused page landing in a free ring slot, which keeps the loop
+    // body and the load counter the same for all steps.
+    auto step = [&](int tile, auto has_prev, auto has_next, auto mask_next, auto with_dma, auto phase, auto pp) {
         // Tile t+1 must have landed (only this wave's loads of one later tile may still be in
         // flight), and every wave must be done with the slots about to be overwritten (K of
         // tile t-1, V of tile t-2).
 #ifdef SARATHI_TRACE
-        const bool tracer = blockIdx.x == 8 && tid == 0 && (tile - tile_begin) < 64;
-        uint32_t *trace = reinterpret_cast<uint32_t *>(p.part_o) + (tile - tile_begin) * 8;
+        const bool tracer = blockIdx.x == 8 && tid == SARATHI_TRACE && (tile - tile_begin) < 64;
+        uint32_t *trace = reinterpret_cast<uint32_t *>(p.part_o) + ((size_t)32768 * p.num_kv_heads * D - 1024) + (tile - tile_begin) * 8;
         if (tracer) trace[0] = (uint32_t)__builtin_amdgcn_s_memtime();
 #endif
-        if (tile + my_ahead - 1 < tile_end) SARATHI_WAIT_VMCNT(LOADS_PER_PAGE); else SARATHI_WAIT_VMCNT(0);
+        if (decltype(with_dma)::value) SARATHI_WAIT_VMCNT(LOADS_PER_PAGE); else SARATHI_WAIT_VMCNT(0);
 #ifdef SARATHI_TRACE
         if (tracer) trace[1] = (uint32_t)__builtin_amdgcn_s_memtime();
 #endif
@@ -627,11 +695,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
 #ifdef SARATHI_TRACE
         if (tracer) trace[2] = (uint32_t)__builtin_amdgcn_s_memtime();
 #endif
-        if (tile + my_ahead < tile_end) issue_page(tile + my_ahead, pg_next);
-        pg_next = page_of(min(tile + my_ahead + 1, tile_end - 1));  // used by the next step
-#ifdef SARATHI_TRACE
-        if (tracer) trace[3] = (uint32_t)__builtin_amdgcn_s_memtime();
-#endif
+        const int rel = tile - tile_begin;
+        if (decltype(with_dma)::value) {
+            issue_page(tile + my_ahead, page_clamp(pg_next));
+            pg_next = page_raw(tile + my_ahead + 1);  // looked at in the next step only
+        }
         // raise the softmax reference if this tile exceeds it by more than the slack (rare)
         if (__any(st.tmax > st.m_ref + kRescaleSlack)) {
             const float m_new = fmaxf(st.m_ref, st.tmax);
@@ -641,31 +709,46 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
 #pragma unroll
             for (int c = 0; c < NB; ++c) st.oacc[c] *= alpha;
         }
-        const int rel = tile - tile_begin;
         const int next_key0 = (tile + 1) * kTileKeys + h * 8;
 #ifdef SARATHI_TRACE
-        if (tracer) trace[4] = (uint32_t)__builtin_amdgcn_s_memtime();
+        if (tracer) trace[3] = (uint32_t)__builtin_amdgcn_s_memtime();
 #endif
-        chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value>(
-            st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE, ((rel + 3) & (kRing - 1)) * TE, scale,
-            next_key0, pos_eff);
+        constexpr int kPhase = decltype(phase)::value;
+        chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value, kPhase,
+                   decltype(pp)::value, (kPhase >= 0)>(st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE,
+                                                      ((rel + 3) & (kRing - 1)) * TE, scale, next_key0, pos_eff);
 #ifdef SARATHI_TRACE
-        if (tracer) trace[5] = (uint32_t)__builtin_amdgcn_s_memtime();
+        if (tracer) trace[4] = (uint32_t)__builtin_amdgcn_s_memtime();
 #endif
     };
     using T = std::true_type;
     using F = std::false_type;
+    using DYN = std::integral_constant<int, -1>;  // ring slots taken from the tile index at run time
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
     if (n_tiles == 1) {
-        step(tile_begin, F{}, F{}, F{});
+        step(tile_begin, F{}, F{}, F{}, F{}, DYN{}, P0{});
     } else {
         // first tile: nothing to accumulate yet
-        if (tile_begin + 1 >= mask_from) step(tile_begin, F{}, T{}, T{}); else step(tile_begin, F{}, T{}, F{});
-        // steady state: unmasked tiles, then the tiles on the causal diagonal
+        if (tile_begin + 1 >= mask_from) step(tile_begin, F{}, T{}, T{}, T{}, DYN{}, P0{});
+        else step(tile_begin, F{}, T{}, F{}, T{}, DYN{}, P0{});
+        // steady state, unmasked tiles: groups of four steps with the ring slots and the register
+        // sets compiled in (the group starts at tile index 1 modulo 4 and leaves the state in set 0),
+        // then single steps up to the causal diagonal
         int tile = tile_begin + 1;
-        for (; tile + 1 < tile_end && tile + 1 < mask_from; ++tile) step(tile, T{}, T{}, F{});
-        for (; tile + 1 < tile_end; ++tile) step(tile, T{}, T{}, T{});
-        // last tile: no further scores to form
-        step(tile_end - 1, T{}, F{}, F{});
+        for (; tile + 4 < tile_end && tile + 4 < mask_from; tile += 4) {
+            step(tile, T{}, T{}, F{}, T{}, P1{}, P0{});
+            step(tile + 1, T{}, T{}, F{}, T{}, P2{}, P1{});
+            step(tile + 2, T{}, T{}, F{}, T{}, P3{}, P0{});
+            step(tile + 3, T{}, T{}, F{}, T{}, P0{}, P1{});
+        }
+        for (; tile + 1 < tile_end && tile + 1 < mask_from; ++tile) step(tile, T{}, T{}, F{}, T{}, DYN{}, P0{});
+        // the tiles on the causal diagonal
+        for (; tile + 1 < tile_end; ++tile) step(tile, T{}, T{}, T{}, T{}, DYN{}, P0{});
+        // last tile: no further scores to form, nothing more to fetch (and no load left in flight after it)
+        step(tile_end - 1, T{}, F{}, F{}, F{}, DYN{}, P0{});
     }
     // Epilogue: the output MFMAs of the last tile.  Only here can a tile hold slots at or beyond
     // ctx_len (a unit never extends past the sequence), whose V bits must be zeroed: stale cache
@@ -685,7 +768,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
                     for (int w = 0; w < 4; ++w)
                         v[w] &= ((key0 + 2 * w < ctx) ? 0x0000FFFFu : 0u) | ((key0 + 2 * w + 1 < ctx) ? 0xFFFF0000u : 0u);
                 }
-                st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), st.p_prev[u],
+                st.oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), st.p[0][u],
                                                                       st.oacc[c], 0, 0, 0);
             }
         }
