@@ -38,6 +38,10 @@ struct sarathi_handle {
     // call gets the same description, so its plan rides along in the append's copy.  Valid while
     // `resident_*` describe what the metadata region of `resident_ws` holds.
     void *resident_ws = nullptr;
+    // workspace whose scheduling words this handle has zeroed, and the launch counter that
+    // alternates the two sets of queue heads
+    const void *sched_ws = nullptr;
+    uint32_t sched_epoch = 0;
     void *resident_stream = nullptr;
     std::vector<int32_t> resident_desc;  // q_len | ctx_len of the planned batch
     uint64_t resident_opt_version = 0;
@@ -204,6 +208,11 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
     if (std::strcmp(name, "tile_split_keys") == 0) {
         if (value < 0 || value > (1 << 24)) return fail(h, SARATHI_EINVAL, "tile_split_keys out of range");
         h->opt.tile_split_keys = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "resident_chunks") == 0) {
+        if (value < -1 || value > 1) return fail(h, SARATHI_EINVAL, "resident_chunks must be -1, 0 or 1");
+        h->opt.resident_chunks = value;
         return SARATHI_OK;
     }
     if (std::strcmp(name, "chunk_blocks_per_cu") == 0) {
@@ -417,6 +426,8 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.num_tile_reduce_units = pl.num_tile_reduce_units;
     m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
+    m.sched = reinterpret_cast<int32_t *>(ws + h->ws.sched);
+    m.sched_epoch = 0;
     // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
     // has both they run side by side: the chunk kernel is forked onto a second stream, where the
     // merge of its own split tiles follows it (hidden behind the longer wave kernel).
@@ -442,9 +453,28 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         if (e == hipSuccess) e = hipEventRecord(h->join_event, h->side_stream);
         if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, 0, stream);
         if (e == hipSuccess) e = hipStreamWaitEvent(s, h->join_event, 0);
+    } else if (both && h->opt.interleave == 2) {
+        // Run-time roles pay (a few atomics per block) when chunk blocks would otherwise pile up two
+        // to a compute unit for a good part of the launch: more chunk blocks than units, and chunk
+        // work (one block per unit, ~0.65 us per 32-key step) that is not small next to the time the
+        // decodes need to stream (~5 bytes/ps).
+        const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
+        const double wave_us = (double)pl.wave_keys * h->cfg.num_kv_heads * h->cfg.head_dim * 4.0 / 5.0e6;
+        const bool many_chunk_blocks = (int64_t)pl.num_tile_units * h->cfg.num_kv_heads > kChunkBlocksForRoles &&
+                                       chunk_us > 0.25 * wave_us;
+        const bool roles = h->cfg.num_kv_heads <= kSchedMaxKvHeads &&
+                           (h->opt.resident_chunks == 1 || (h->opt.resident_chunks < 0 && many_chunk_blocks));
+        if (roles) {
+            if (h->sched_ws != workspace) {  // first use of this workspace: the scheduling words start at zero
+                e = (hipError_t)launch_zero(m.sched, kSchedBytes, stream);
+                if (e != hipSuccess) return hip_fail(h, "launch zero fill", e);
+                h->sched_ws = workspace;
+            }
+            m.sched_epoch = h->sched_epoch++;
+        }
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, roles ? 5 : 4, 0, stream);
     } else {
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out,
-                                         both && h->opt.interleave == 2 ? 4 : 3, 0, stream);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, 0, stream);
     }
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);

@@ -80,6 +80,8 @@ struct AttnParams {
     int32_t num_tile_units;  // units [0, num_tile_units) are 128-column chunk tiles (one block each)
     int32_t num_units;       // the rest are 16-column wave tiles (four per block)
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
+    int32_t *sched;          // scheduling words of the run-time role assignment (else unused)
+    uint32_t sched_epoch;
 };
 
 // What one work unit (tile, split) covers.
@@ -839,25 +841,81 @@ __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
     }
 }
 
-// Both kinds of unit in ONE launch: the first num_tile_units * Hkv blocks run chunk tiles, the
-// rest wave tiles (block-uniform branch).  Saves the second stream's fork and join.
-template <int D>
+// Both kinds of unit in ONE launch (saves the second stream's fork and join).
+//
+// ROLES == false: the first num_tile_units * Hkv blocks run chunk tiles, the rest wave tiles.
+//
+// ROLES == true: a block decides what it runs when it starts.  Chunk blocks are compute-bound and
+// wave blocks memory-bound, and they overlap only when they share a compute unit; two chunk blocks
+// on one unit leave it without a memory stream.  So each block looks up its compute unit (hardware
+// id registers), tries to become that unit's one chunk block (compare-and-swap on the unit's flag)
+// and otherwise takes wave tiles; work is handed out by per-KV-head queue heads (atomic adds), each
+// kind longest first, and a block whose preferred queue is empty takes from the other one.  The grid
+// has exactly one block per work item and KV head, so the second queue cannot be empty too.  All
+// atomics are relaxed: they only hand out indices into the read-only plan.  The launch clears the
+// queue heads of the next launch (two sets used alternately); the flags return to zero by themselves.
+template <int D, bool ROLES>
 __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
     const int kvh = blockIdx.x % p.num_kv_heads;
     int blk = blockIdx.x / p.num_kv_heads;
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
-    if (blk < p.num_tile_units) {
-        const uint32_t u = p.units[blk];
-        chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
-    } else {
-        blk -= p.num_tile_units;
-        const int idx = p.num_tile_units + blk * 4 + (threadIdx.x >> 6);
-        if (idx < p.num_units) {
-            const uint32_t u = p.units[idx];
-            wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
+    const int n_wave_blocks = (p.num_units - p.num_tile_units + 3) / 4;
+    bool chunk_role = blk < p.num_tile_units;
+    __shared__ int32_t role[3];  // kind, index, "this block set its compute unit's flag"
+    // compute unit, shader array and shader engine ids (bits 8..15 of HW_ID) and the XCC id
+    auto my_cu_flag = [&]() -> int32_t * {
+        const uint32_t hw = __builtin_amdgcn_s_getreg((7 << 11) | (8 << 6) | 4);
+        const uint32_t xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);
+        return p.sched + (((xcc << 8) | hw) & (kSchedCuSlots - 1));
+    };
+    if (ROLES) {
+        if (threadIdx.x == 0) {
+            int32_t *flag = my_cu_flag();
+            int32_t *heads = p.sched + kSchedCuSlots + (p.sched_epoch & 1) * 2 * kSchedMaxKvHeads;
+            if (blk == 0) {  // queue heads of the next launch
+                int32_t *other = p.sched + kSchedCuSlots + ((p.sched_epoch + 1) & 1) * 2 * kSchedMaxKvHeads;
+                __hip_atomic_store(other + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(other + kSchedMaxKvHeads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            int32_t expected = 0;
+            const bool own = __hip_atomic_compare_exchange_strong(flag, &expected, 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                                  __HIP_MEMORY_SCOPE_AGENT);
+            role[2] = own ? 1 : 0;
+            int kind = own ? 1 : 0;  // 1 = chunk tiles, 0 = wave tiles
+            int idx = __hip_atomic_fetch_add(heads + kind * kSchedMaxKvHeads + kvh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (idx >= (kind ? p.num_tile_units : n_wave_blocks)) {
+                kind ^= 1;
+                idx = __hip_atomic_fetch_add(heads + kind * kSchedMaxKvHeads + kvh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (idx >= (kind ? p.num_tile_units : n_wave_blocks)) idx = -1;  // cannot happen: one block per item
+            }
+            role[0] = kind;
+            role[1] = idx;
+        }
+        __syncthreads();
+        chunk_role = role[0] != 0;
+        blk = role[1];
+        if (blk >= 0 && !chunk_role) blk += p.num_tile_units;  // same numbering as the static split below
+    }
+    if (blk >= 0) {
+        if (chunk_role) {
+            const uint32_t u = p.units[blk];
+            chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
+        } else {
+            const int idx = p.num_tile_units + (blk - p.num_tile_units) * 4 + (threadIdx.x >> 6);
+            if (idx < p.num_units) {
+                const uint32_t u = p.units[idx];
+                wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
+            }
         }
     }
+    if (ROLES && threadIdx.x == 0 && role[2])
+        __hip_atomic_store(my_cu_flag(), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void zero_words_kernel(uint32_t *p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -990,6 +1048,14 @@ int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void 
     return (int)hipGetLastError();
 }
 
+int launch_zero(void *ptr, size_t bytes, void *stream) {
+    const size_t n = bytes / 4;
+    if (n == 0) return (int)hipSuccess;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t *>(ptr), n);
+    return (int)hipGetLastError();
+}
+
 int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream) {
     if (count <= 0) return (int)hipSuccess;
     static_assert(kMergeCols == kReduceCols, "planner and merge kernel must agree on columns per block");
@@ -1033,14 +1099,22 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.num_tile_units = m.num_tile_units;
     p.num_units = m.num_units;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
+    p.sched = nullptr;
+    p.sched_epoch = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
     const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
-    if (which == 4) {
-        if (cfg.head_dim == 128)
-            hipLaunchKernelGGL(attn_hybrid_kernel<128>, dim3(chunk_blocks + wave_blocks), dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL(attn_hybrid_kernel<64>, dim3(chunk_blocks + wave_blocks), dim3(256), 0, st, p);
+    if (which == 4 || which == 5) {
+        p.sched = m.sched;
+        p.sched_epoch = m.sched_epoch;
+        const dim3 grid(chunk_blocks + wave_blocks);
+        if (cfg.head_dim == 128) {
+            if (which == 5) hipLaunchKernelGGL((attn_hybrid_kernel<128, true>), grid, dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((attn_hybrid_kernel<128, false>), grid, dim3(256), 0, st, p);
+        } else {
+            if (which == 5) hipLaunchKernelGGL((attn_hybrid_kernel<64, true>), grid, dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((attn_hybrid_kernel<64, false>), grid, dim3(256), 0, st, p);
+        }
         return (int)hipGetLastError();
     }
     if (chunk_blocks && (which & 1)) {

@@ -18,6 +18,13 @@ constexpr int kTileCols = 128;    // query columns a chunk tile carries (4 waves
 constexpr int kReduceCols = 8;    // columns one block of the merge kernel handles
 constexpr int kKindWave = 0;
 constexpr int kKindTile = 1;
+// Scheduling words of the one-launch hybrid kernel when blocks pick their role at run time:
+// one "a chunk block lives here" flag per compute unit (indexed by hardware ids), then two
+// alternating sets of per-KV-head queue heads [set][kind][kv head].
+constexpr int kSchedCuSlots = 4096;
+constexpr int kSchedMaxKvHeads = 128;
+constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 2 * 2 * kSchedMaxKvHeads);
+constexpr int kChunkBlocksForRoles = 256;   // one per compute unit
 
 // One tile of query columns of one sequence.  A "column" is one (query row, query head inside
 // a KV group) pair: col = row*G + head_in_group.  Its key range 0..n_keys-1 is cut into
@@ -54,12 +61,15 @@ struct Plan {
     int32_t num_part_rows = 0;
     int32_t split_keys = 0;
     int32_t tile_split_keys = 0;
+    int64_t tile_unit_steps = 0;      // 32-key steps summed over the chunk-tile units
+    int64_t wave_keys = 0;            // keys summed over the wave tiles
 };
 
 // Byte offsets of the regions inside the caller's workspace (all 256-byte aligned).
 struct WorkspaceLayout {
     size_t meta;          // per-call metadata, packed: sequence arrays + hints (append) or tile descriptors + units (attention)
     size_t meta_bytes;
+    size_t sched;         // int32 [kSchedCuSlots + 2*2*kSchedMaxKvHeads], zero between launches
     size_t part_ml;       // float [max_part_rows][Hkv][2]
     size_t part_o;        // float [max_part_rows][Hkv][head_dim]
     size_t total;
@@ -77,6 +87,9 @@ struct Options {
     int64_t plan_at_append = 1;     // sarathi_kv_append also plans and uploads the attention metadata of its batch
     int64_t interleave = 2;         // batches with both kinds of tile: 0 = two launches in sequence, 1 = chunk kernel on a
                                     // second stream next to the wave kernel, 2 = one launch holding both kinds of block
+    int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
+                                    // a compute unit holds at most one chunk block while decode work remains
+                                    // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)
     int64_t chunk_blocks_per_cu = 0; // side-stream mode: 1 = pad the chunk kernel's LDS so that one block fits a compute
                                     // unit (leaves the other block slot to the wave kernel), 2 = no padding, 0 = automatic
 };
@@ -127,14 +140,20 @@ struct AttnMeta {
     int32_t num_tile_reduce_units;   // leading entries of reduce_units that belong to chunk tiles
     float *part_ml;              // dev
     float *part_o;               // dev
+    int32_t *sched;              // dev, kSchedBytes
+    uint32_t sched_epoch;        // which of the two queue-head sets this launch uses (the other one is cleared by it)
 };
 
-// which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch
+// which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch,
+// 5 = one launch whose blocks take their role at run time (needs m.sched zeroed once, see launch_zero)
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
                      const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, int chunk_lds_pad,
                      void *stream);
 
 // Merges the split tiles named by reduce_units[first .. first+count).
+// Fills `bytes` (a multiple of 4) at `ptr` with zeros by a small kernel (no memset node: callers may capture).
+int launch_zero(void *ptr, size_t bytes, void *stream);
+
 int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream);
 
 }  // namespace sarathi

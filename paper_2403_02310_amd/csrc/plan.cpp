@@ -44,6 +44,7 @@ WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
     w.meta = off;
     w.meta_bytes = align_up(align_up(append_meta, 256) + attn_meta, 256);  // an append may carry both
     off += w.meta_bytes;
+    w.sched = off;     off = align_up(off + kSchedBytes, 256);
     w.part_ml = off;   off = align_up(off + sizeof(float) * 2 * (size_t)w.max_part_rows * cfg.num_kv_heads, 256);
     w.part_o = off;    off = align_up(off + sizeof(float) * (size_t)w.max_part_rows * cfg.num_kv_heads * cfg.head_dim, 256);
     w.total = off;
@@ -209,6 +210,14 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         tile_floor = std::max<int64_t>(2 * kMinTileSplitKeys, (int64_t)(wave_us / 1.2) * kTileKeys);
     }
     int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], tile_units_wanted, tile_floor);
+    if (opt.tile_split_keys <= 0 && !has_wave_tiles) {
+        // Balance: with few, long chunk tiles the longest unit must stay well below a block slot's
+        // share of the work (2 slots on each of 256 compute units), or the tail of the launch runs
+        // on a few units only.  0.42 of the share measured best on the long-context chunk batch.
+        const int64_t share = keys_of_kind[kKindTile] * cfg.num_kv_heads / 512;
+        const int64_t balanced = ceil_div(std::max<int64_t>(tile_floor, share * 42 / 100), kTileKeys) * kTileKeys;
+        tile_split = std::min(tile_split, balanced);
+    }
     for (;;) {
         int64_t n_split_units = 0, rows = 0, n_split_tiles = 0;
         count_splits(plan, 0, n_chunk_tiles, tile_split, n_split_units, rows, n_split_tiles);
@@ -230,6 +239,9 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     emit_units(plan, 0, n_chunk_tiles, tile_split, scratch, bucket);
     plan.num_tile_units = (int32_t)plan.units.size();
     plan.num_tile_reduce_units = (int32_t)plan.reduce_units.size();
+    plan.tile_unit_steps = 0;
+    for (size_t ti = 0; ti < n_chunk_tiles; ++ti) plan.tile_unit_steps += ceil_div(plan.tiles[ti].n_keys, kTileKeys) + plan.tiles[ti].n_splits - 1;
+    plan.wave_keys = keys_of_kind[kKindWave];
     emit_units(plan, n_chunk_tiles, plan.tiles.size(), wave_split, scratch, bucket);
 }
 

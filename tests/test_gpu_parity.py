@@ -112,13 +112,36 @@ def test_chunk_tiles_with_forced_splits_and_both_paths(hx, shape):
     for opts in ({"tile_split_keys": 64, "split_keys": 32}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20},
                  {"interleave": 0, "tile_split_keys": 128}, {"interleave": 1, "tile_split_keys": 128},
                  {"interleave": 1, "chunk_blocks_per_cu": 2, "tile_split_keys": 128},
-                 {"interleave": 2, "tile_split_keys": 128}):
+                 {"interleave": 2, "tile_split_keys": 128}, {"interleave": 2, "resident_chunks": 1, "tile_split_keys": 128},
+                 {"interleave": 2, "resident_chunks": 1}):
         h = hx.make_handle(b)
         for k, v in opts.items():
             h.set_option(k, v)
         print("options", opts, flush=True)
         out = hx.bf16_tensor_to_f64(hx.setup_and_run(b, 0x7FC1, handle=h)["out"])
         compare(out, ref, str(opts))
+
+
+def test_run_time_roles_repeat_on_one_workspace(hx):
+    """Blocks that pick chunk or wave tiles when they start (per-unit flags and queue heads in the workspace):
+    several launches in a row on one handle and workspace, each against the checker and equal bit for bit."""
+    s = SHAPES["gqa4_d128"]
+    b = wl._make("roles", s, [200, 150, 1, 1, 1, 9, 1], [900, 150, 700, 33, 1200, 64, 300], 83)
+    h = hx.make_handle(b)
+    h.set_option("resident_chunks", 1)
+    h.set_option("tile_split_keys", 256)
+    st = hx.setup_and_run(b, 0x7FC1, handle=h)
+    ref = oracle.attention_for_batch(b)
+    first = hx.bf16_tensor_to_f64(st["out"])
+    compare(first, ref, "roles launch 0")
+    k_new, v_new = hx.new_token_kv(b, st["kv_host"])
+    k_new, v_new = hx.bits_to_device(k_new), hx.bits_to_device(v_new)
+    for i in range(1, 5):
+        out = hx.run_iteration(h, b, st["k_cache"], st["v_cache"], st["bt"], st["q"], k_new, v_new)
+        torch.cuda.synchronize()
+        got = hx.bf16_tensor_to_f64(out)
+        compare(got, ref, "roles launch %d" % i)
+        np.testing.assert_array_equal(got, first)
 
 
 def test_chunking_invariance_config1(hx):
