@@ -32,11 +32,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 
-def make_workload(name: str):
+def make_workload(name: str, seed=None):
     from paper_2403_02310_amd import workloads as wl
     base = name.split("_")[0]
-    full = {"c1": wl.config1_tiny, "c2": wl.config2_mistral_hybrid, "c3": wl.config3_decode_only,
-            "c4": wl.config4_yi_long, "c5": wl.config5_llama70b}[base]()
+    make = {"c1": wl.config1_tiny, "c2": wl.config2_mistral_hybrid, "c3": wl.config3_decode_only,
+            "c4": wl.config4_yi_long, "c5": wl.config5_llama70b}[base]
+    full = make() if seed is None else make(seed=seed)
     batch = wl.decodes_first(full)
     if name.endswith("_chunk") or name.endswith("_chunks"):
         batch = batch.sub_batch([i for i in range(batch.num_seqs) if batch.q_len[i] > 1], name)
@@ -54,12 +55,84 @@ def make_workload(name: str):
     return batch, desc
 
 
+def run_sweep(args, binding, harness, torch) -> int:
+    """Chunk-size sweep (section 5.4's ablation shape): one 8192-token prompt at the LLaMA2-70B attention shape
+    prefilled in chunks of c tokens, N = 8192/c iterations of KV append + attention; total time per c."""
+    from paper_2403_02310_amd import workloads as wl
+    prompt = 8192
+    last = wl.config5_sweep(prompt)[-1]
+    s = last.shape
+    k_all, v_all = last.kv_bits(0)
+    q_all = wl.normal_bf16((55, 0x51, 7), (prompt, s.num_q_heads, s.head_dim))
+    q_dev, k_dev, v_dev = (harness.bits_to_device(x) for x in (q_all, k_all, v_all))
+    out = torch.empty_like(q_dev)
+    bt = torch.from_numpy(last.block_table).cuda()
+    k_cache, v_cache = harness.make_pools(last, 0)
+    handle = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=prompt, max_seqs=8,
+                            max_blocks_per_seq=last.max_blocks_per_seq)
+    for kv in args.opt:
+        name, value = kv.split("=")
+        handle.set_option(name, int(value))
+    ws = handle.ensure_workspace()
+    stream = torch.cuda.current_stream().cuda_stream
+    lib, h = binding.lib, handle._h
+    i32 = ctypes.c_int32 * 1
+    row_q = s.num_q_heads * s.head_dim * 2
+    row_kv = s.num_kv_heads * s.head_dim * 2
+    flops = 4.0 * s.head_dim * s.num_q_heads * (prompt * (prompt + 1) / 2)
+    reps = max(3, min(args.steps, 10))
+    curve = {}
+    for c in (8192, 2048, 1024, 512, 256, 128, 64):
+        n_it = prompt // c
+        qs, ql, cl = i32(0), i32(c), [i32((i + 1) * c) for i in range(n_it)]
+
+        def one_pass():
+            for i in range(n_it):
+                off = i * c
+                st = lib.sarathi_kv_append(h, k_dev.data_ptr() + off * row_kv, v_dev.data_ptr() + off * row_kv,
+                                           k_cache.data_ptr(), v_cache.data_ptr(), bt.data_ptr(), qs, ql, cl[i], 1, c,
+                                           last.num_pages, ws.data_ptr(), stream)
+                if st == 0:
+                    st = lib.sarathi_hybrid_attention(h, q_dev.data_ptr() + off * row_q, k_cache.data_ptr(), v_cache.data_ptr(),
+                                                      bt.data_ptr(), qs, ql, cl[i], 1, c, last.num_pages,
+                                                      float(last.sm_scale), out.data_ptr() + off * row_q, ws.data_ptr(), stream)
+                if st != 0:
+                    raise RuntimeError("sweep step failed: %s" % handle.last_error())
+
+        one_pass()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            one_pass()
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) * 1e6)
+        us = float(np.median(times))
+        curve[str(c)] = {"iterations": n_it, "total_us": us, "mfma_frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    one_shot = curve["8192"]["total_us"]
+    for v in curve.values():
+        v["overhead_vs_one_shot"] = v["total_us"] / one_shot
+    best = curve["2048"]
+    print(json.dumps({
+        "metric": "chunked prefill of one 8192-token prompt (KV append + attention per chunk): prompt tokens/s at chunk 2048",
+        "value": prompt / (best["total_us"] * 1e-6), "unit": "tokens/s", "n_gpus": 1, "steps": reps, "warmup": 1,
+        "ms_per_step": best["total_us"] * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c5_sweep: LLaMA2-70B shape (Hq64/Hkv8/d128), one 8192-token prompt, chunk sizes 64..2048 and one shot",
+                   "algorithmic_flops": flops},
+        "sweep": curve}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c2",
+                    help="c2 (default), c3, c4, c5, <cN>_chunks, <cN>_decodes, or c5_sweep (one 8192-token prompt "
+                         "prefilled in chunks of 64 ... 2048 and in one shot)")
+    ap.add_argument("--seed", type=int, default=None, help="seed of the workload recipe (default: the recipe's own)")
     ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
@@ -77,7 +150,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     from paper_2403_02310_amd import binding, harness
 
-    batch, desc = make_workload(args.workload)
+    if args.workload == "c5_sweep":
+        return run_sweep(args, binding, harness, torch)
+    batch, desc = make_workload(args.workload, args.seed)
     s = batch.shape
     T, S = batch.num_tokens, batch.num_seqs
     kv_bytes_per_copy = 2 * batch.num_pages * s.num_kv_heads * s.page_size * s.head_dim * 2

@@ -101,8 +101,7 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * on a second stream next to the wave-tile kernel, 2 = one launch holding both kinds of block),
  * "resident_chunks" (one-launch mode: blocks choose between chunk and wave tiles when they start so
  * that a compute unit runs at most one chunk block while decode work remains; -1 = automatic, 0 =
- * never, 1 = always), "chunk_blocks_per_cu" (second-stream mode: 1 pads the chunk kernel's LDS so
- * that one block fits a compute unit, 2 no padding, 0 automatic),
+ * never, 1 = always),
  * "time_kernels" (0/1/2, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);

@@ -38,10 +38,8 @@ struct sarathi_handle {
     // call gets the same description, so its plan rides along in the append's copy.  Valid while
     // `resident_*` describe what the metadata region of `resident_ws` holds.
     void *resident_ws = nullptr;
-    // workspace whose scheduling words this handle has zeroed, and the launch counter that
-    // alternates the two sets of queue heads
+    // workspace whose scheduling words this handle has zeroed
     const void *sched_ws = nullptr;
-    uint32_t sched_epoch = 0;
     void *resident_stream = nullptr;
     std::vector<int32_t> resident_desc;  // q_len | ctx_len of the planned batch
     uint64_t resident_opt_version = 0;
@@ -94,9 +92,6 @@ sarathi_status acquire_slot(sarathi_handle *h, int *slot) {
 }
 
 constexpr size_t kMaxTimedLaunches = 8192;
-// Extra dynamic LDS that makes a chunk-kernel block (64 KB static) too large for two to share a
-// compute unit's 160 KB.
-constexpr int kChunkLdsPad = 24 * 1024;
 
 // Records the start event of a timed launch; returns the pair index or -1 when timing is off/full.
 int timing_begin(sarathi_handle *h, int kind, hipStream_t s) {
@@ -213,11 +208,6 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
     if (std::strcmp(name, "resident_chunks") == 0) {
         if (value < -1 || value > 1) return fail(h, SARATHI_EINVAL, "resident_chunks must be -1, 0 or 1");
         h->opt.resident_chunks = value;
-        return SARATHI_OK;
-    }
-    if (std::strcmp(name, "chunk_blocks_per_cu") == 0) {
-        if (value < 0 || value > 2) return fail(h, SARATHI_EINVAL, "chunk_blocks_per_cu must be 0, 1 or 2");
-        h->opt.chunk_blocks_per_cu = value;
         return SARATHI_OK;
     }
     if (std::strcmp(name, "tile_min_cols") == 0) {
@@ -427,7 +417,6 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     m.sched = reinterpret_cast<int32_t *>(ws + h->ws.sched);
-    m.sched_epoch = 0;
     // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
     // has both they run side by side: the chunk kernel is forked onto a second stream, where the
     // merge of its own split tiles follows it (hidden behind the longer wave kernel).
@@ -446,12 +435,11 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         e = hipEventRecord(h->fork_event, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(h->side_stream, h->fork_event, 0);
         if (e != hipSuccess) return hip_fail(h, "fork to side stream", e);
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1,
-                                         h->opt.chunk_blocks_per_cu == 2 ? 0 : kChunkLdsPad, h->side_stream);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1, h->side_stream);
         if (e == hipSuccess) e = (hipError_t)launch_reduce(h->cfg, m, out, 0, m.num_tile_reduce_units, h->side_stream);
         merged_on_side = m.num_tile_reduce_units;
         if (e == hipSuccess) e = hipEventRecord(h->join_event, h->side_stream);
-        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, 0, stream);
+        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, stream);
         if (e == hipSuccess) e = hipStreamWaitEvent(s, h->join_event, 0);
     } else if (both && h->opt.interleave == 2) {
         // Run-time roles pay (a few atomics per block) when chunk blocks would otherwise pile up two
@@ -470,11 +458,10 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
                 if (e != hipSuccess) return hip_fail(h, "launch zero fill", e);
                 h->sched_ws = workspace;
             }
-            m.sched_epoch = h->sched_epoch++;
         }
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, roles ? 5 : 4, 0, stream);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, roles ? 5 : 4, stream);
     } else {
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, 0, stream);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, stream);
     }
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);

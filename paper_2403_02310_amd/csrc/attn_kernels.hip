@@ -81,7 +81,6 @@ struct AttnParams {
     int32_t num_units;       // the rest are 16-column wave tiles (four per block)
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
     int32_t *sched;          // scheduling words of the run-time role assignment (else unused)
-    uint32_t sched_epoch;
 };
 
 // What one work unit (tile, split) covers.
@@ -381,16 +380,13 @@ struct ChunkSlot {
     bool is_score;
     int sub;
 };
-#ifndef SARATHI_MFMA_ORDER
-#define SARATHI_MFMA_ORDER 1
-#endif
 constexpr ChunkSlot chunk_slot(int i, int n_s, int n_o) {
     int sc = 0, ou = 0;
     for (int k = 0;; ++k) {
         bool pick_s = false;
         if (sc >= n_s) pick_s = false;
         else if (ou >= n_o) pick_s = true;
-        else pick_s = SARATHI_MFMA_ORDER == 0 ? (k % 2 == 0) : (k % 3 != 2);
+        else pick_s = k % 3 != 2;
         if (k == i) return ChunkSlot{pick_s, pick_s ? sc : ou};
         if (pick_s) ++sc; else ++ou;
     }
@@ -419,10 +415,7 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
     constexpr int N_S = HAS_NEXT ? NS : 0;              // score MFMAs (one dependent chain through s_next)
     constexpr int N_O = HAS_PREV ? 2 * NB : 0;          // output MFMAs (NB accumulators, two pages each)
     constexpr int NM = N_S + N_O;
-#ifndef SARATHI_AHEAD
-#define SARATHI_AHEAD 3
-#endif
-    constexpr int AHEAD = SARATHI_AHEAD;                 // operand reads run this many MFMAs ahead
+    constexpr int AHEAD = 3;                             // operand reads run this many MFMAs ahead
     auto is_score = [&](int i) { return chunk_slot(i, N_S, N_O).is_score; };
     auto sub_index = [&](int i) { return chunk_slot(i, N_S, N_O).sub; };
 
@@ -553,12 +546,6 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     constexpr int LOADS_PER_PAGE = PAGE_ELEMS / 512;  // 1 KiB wavefront loads per page of one KV head
     using SM = ChunkSmem<D>;
     constexpr int TE = SM::kTileElems;
-#ifndef SARATHI_CHUNK_PRIO
-#define SARATHI_CHUNK_PRIO 3
-#endif
-    // Chunk waves are latency-bound chains of dependent steps; the decode waves they may share a
-    // SIMD with are memory-bound and have issue slots to spare.  Issue priority goes to the chunk.
-    __builtin_amdgcn_s_setprio(SARATHI_CHUNK_PRIO);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; tell the compiler
@@ -683,20 +670,9 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         // Tile t+1 must have landed (only this wave's loads of one later tile may still be in
         // flight), and every wave must be done with the slots about to be overwritten (K of
         // tile t-1, V of tile t-2).
-#ifdef SARATHI_TRACE
-        const bool tracer = blockIdx.x == 8 && tid == SARATHI_TRACE && (tile - tile_begin) < 64;
-        uint32_t *trace = reinterpret_cast<uint32_t *>(p.part_o) + ((size_t)32768 * p.num_kv_heads * D - 1024) + (tile - tile_begin) * 8;
-        if (tracer) trace[0] = (uint32_t)__builtin_amdgcn_s_memtime();
-#endif
         if (decltype(with_dma)::value) SARATHI_WAIT_VMCNT(LOADS_PER_PAGE); else SARATHI_WAIT_VMCNT(0);
-#ifdef SARATHI_TRACE
-        if (tracer) trace[1] = (uint32_t)__builtin_amdgcn_s_memtime();
-#endif
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-#ifdef SARATHI_TRACE
-        if (tracer) trace[2] = (uint32_t)__builtin_amdgcn_s_memtime();
-#endif
         const int rel = tile - tile_begin;
         if (decltype(with_dma)::value) {
             issue_page(tile + my_ahead, page_clamp(pg_next));
@@ -712,16 +688,10 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
             for (int c = 0; c < NB; ++c) st.oacc[c] *= alpha;
         }
         const int next_key0 = (tile + 1) * kTileKeys + h * 8;
-#ifdef SARATHI_TRACE
-        if (tracer) trace[3] = (uint32_t)__builtin_amdgcn_s_memtime();
-#endif
         constexpr int kPhase = decltype(phase)::value;
         chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value, kPhase,
                    decltype(pp)::value, (kPhase >= 0)>(st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE,
                                                       ((rel + 3) & (kRing - 1)) * TE, scale, next_key0, pos_eff);
-#ifdef SARATHI_TRACE
-        if (tracer) trace[4] = (uint32_t)__builtin_amdgcn_s_memtime();
-#endif
     };
     using T = std::true_type;
     using F = std::false_type;
@@ -817,10 +787,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
 // loop has the registers it needs, the matrix pipe / vector ALU overlap comes from inside the wave.
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(AttnParams p) {
-#ifndef SARATHI_CHUNK_LDS_PAD
-#define SARATHI_CHUNK_LDS_PAD 0
-#endif
-    __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems + SARATHI_CHUNK_LDS_PAD];
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
     const int kvh = blockIdx.x % p.num_kv_heads;  // consecutive blocks = the KV heads of one unit
     const int blk = blockIdx.x / p.num_kv_heads;
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
@@ -852,8 +819,9 @@ __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
 // and otherwise takes wave tiles; work is handed out by per-KV-head queue heads (atomic adds), each
 // kind longest first, and a block whose preferred queue is empty takes from the other one.  The grid
 // has exactly one block per work item and KV head, so the second queue cannot be empty too.  All
-// atomics are relaxed: they only hand out indices into the read-only plan.  The launch clears the
-// queue heads of the next launch (two sets used alternately); the flags return to zero by themselves.
+// atomics are relaxed: they only hand out indices into the read-only plan.  Every block counts itself
+// in after it has taken its item, and the block that completes the count of its KV head puts that
+// head's words back to zero when it ends, so a launch leaves the scheduling words as it found them.
 template <int D, bool ROLES>
 __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
@@ -862,7 +830,7 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
     const int n_wave_blocks = (p.num_units - p.num_tile_units + 3) / 4;
     bool chunk_role = blk < p.num_tile_units;
-    __shared__ int32_t role[3];  // kind, index, "this block set its compute unit's flag"
+    __shared__ int32_t role[4];  // kind, index, "this block set its compute unit's flag", "last block of its KV head to take an item"
     // compute unit, shader array and shader engine ids (bits 8..15 of HW_ID) and the XCC id
     auto my_cu_flag = [&]() -> int32_t * {
         const uint32_t hw = __builtin_amdgcn_s_getreg((7 << 11) | (8 << 6) | 4);
@@ -872,12 +840,7 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     if (ROLES) {
         if (threadIdx.x == 0) {
             int32_t *flag = my_cu_flag();
-            int32_t *heads = p.sched + kSchedCuSlots + (p.sched_epoch & 1) * 2 * kSchedMaxKvHeads;
-            if (blk == 0) {  // queue heads of the next launch
-                int32_t *other = p.sched + kSchedCuSlots + ((p.sched_epoch + 1) & 1) * 2 * kSchedMaxKvHeads;
-                __hip_atomic_store(other + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(other + kSchedMaxKvHeads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            int32_t *heads = p.sched + kSchedCuSlots;
             int32_t expected = 0;
             const bool own = __hip_atomic_compare_exchange_strong(flag, &expected, 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                                   __HIP_MEMORY_SCOPE_AGENT);
@@ -889,8 +852,11 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
                 idx = __hip_atomic_fetch_add(heads + kind * kSchedMaxKvHeads + kvh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (idx >= (kind ? p.num_tile_units : n_wave_blocks)) idx = -1;  // cannot happen: one block per item
             }
+            // the items above are taken (their results were waited for) before this block counts itself in
+            const int arrived = __hip_atomic_fetch_add(heads + 2 * kSchedMaxKvHeads + kvh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             role[0] = kind;
             role[1] = idx;
+            role[3] = arrived == p.num_tile_units + n_wave_blocks - 1;
         }
         __syncthreads();
         chunk_role = role[0] != 0;
@@ -909,8 +875,15 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
             }
         }
     }
-    if (ROLES && threadIdx.x == 0 && role[2])
-        __hip_atomic_store(my_cu_flag(), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ROLES && threadIdx.x == 0) {
+        if (role[2]) __hip_atomic_store(my_cu_flag(), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (role[3]) {  // every block of this KV head has taken its item: nobody reads these words again
+            int32_t *heads = p.sched + kSchedCuSlots;
+            __hip_atomic_store(heads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(heads + kSchedMaxKvHeads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(heads + 2 * kSchedMaxKvHeads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 __global__ void zero_words_kernel(uint32_t *p, size_t n) {
@@ -1078,8 +1051,7 @@ int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32
 }
 
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, int chunk_lds_pad,
-                     void *stream) {
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream) {
     if (m.num_units == 0) return (int)hipSuccess;
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
@@ -1100,13 +1072,11 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.num_units = m.num_units;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
     p.sched = nullptr;
-    p.sched_epoch = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
     const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
     if (which == 4 || which == 5) {
         p.sched = m.sched;
-        p.sched_epoch = m.sched_epoch;
         const dim3 grid(chunk_blocks + wave_blocks);
         if (cfg.head_dim == 128) {
             if (which == 5) hipLaunchKernelGGL((attn_hybrid_kernel<128, true>), grid, dim3(256), 0, st, p);
@@ -1119,9 +1089,9 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     }
     if (chunk_blocks && (which & 1)) {
         if (cfg.head_dim == 128)
-            hipLaunchKernelGGL(attn_chunk_kernel<128>, dim3(chunk_blocks), dim3(256), (size_t)chunk_lds_pad, st, p);
+            hipLaunchKernelGGL(attn_chunk_kernel<128>, dim3(chunk_blocks), dim3(256), 0, st, p);
         else
-            hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), (size_t)chunk_lds_pad, st, p);
+            hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), 0, st, p);
     }
     if (wave_blocks && (which & 2)) {
         if (cfg.head_dim == 128)

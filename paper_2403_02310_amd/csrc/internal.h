@@ -19,11 +19,12 @@ constexpr int kReduceCols = 8;    // columns one block of the merge kernel handl
 constexpr int kKindWave = 0;
 constexpr int kKindTile = 1;
 // Scheduling words of the one-launch hybrid kernel when blocks pick their role at run time:
-// one "a chunk block lives here" flag per compute unit (indexed by hardware ids), then two
-// alternating sets of per-KV-head queue heads [set][kind][kv head].
+// one "a chunk block lives here" flag per compute unit (indexed by hardware ids), then per-KV-head
+// queue heads [kind][kv head] and arrival counts [kv head].  All words are zero between launches:
+// a launch leaves them as it found them.
 constexpr int kSchedCuSlots = 4096;
 constexpr int kSchedMaxKvHeads = 128;
-constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 2 * 2 * kSchedMaxKvHeads);
+constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 3 * kSchedMaxKvHeads);
 constexpr int kChunkBlocksForRoles = 256;   // one per compute unit
 
 // One tile of query columns of one sequence.  A "column" is one (query row, query head inside
@@ -69,7 +70,7 @@ struct Plan {
 struct WorkspaceLayout {
     size_t meta;          // per-call metadata, packed: sequence arrays + hints (append) or tile descriptors + units (attention)
     size_t meta_bytes;
-    size_t sched;         // int32 [kSchedCuSlots + 2*2*kSchedMaxKvHeads], zero between launches
+    size_t sched;         // int32 [kSchedCuSlots + 3*kSchedMaxKvHeads], zero between launches
     size_t part_ml;       // float [max_part_rows][Hkv][2]
     size_t part_o;        // float [max_part_rows][Hkv][head_dim]
     size_t total;
@@ -90,8 +91,6 @@ struct Options {
     int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
                                     // a compute unit holds at most one chunk block while decode work remains
                                     // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)
-    int64_t chunk_blocks_per_cu = 0; // side-stream mode: 1 = pad the chunk kernel's LDS so that one block fits a compute
-                                    // unit (leaves the other block slot to the wave kernel), 2 = no padding, 0 = automatic
 };
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg);
@@ -141,14 +140,12 @@ struct AttnMeta {
     float *part_ml;              // dev
     float *part_o;               // dev
     int32_t *sched;              // dev, kSchedBytes
-    uint32_t sched_epoch;        // which of the two queue-head sets this launch uses (the other one is cleared by it)
 };
 
 // which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch,
 // 5 = one launch whose blocks take their role at run time (needs m.sched zeroed once, see launch_zero)
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
-                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, int chunk_lds_pad,
-                     void *stream);
+                     const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream);
 
 // Merges the split tiles named by reduce_units[first .. first+count).
 // Fills `bytes` (a multiple of 4) at `ptr` with zeros by a small kernel (no memset node: callers may capture).

@@ -111,7 +111,6 @@ def test_chunk_tiles_with_forced_splits_and_both_paths(hx, shape):
     assert info.num_tile_items > 0 and info.num_items > info.num_tile_items
     for opts in ({"tile_split_keys": 64, "split_keys": 32}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20},
                  {"interleave": 0, "tile_split_keys": 128}, {"interleave": 1, "tile_split_keys": 128},
-                 {"interleave": 1, "chunk_blocks_per_cu": 2, "tile_split_keys": 128},
                  {"interleave": 2, "tile_split_keys": 128}, {"interleave": 2, "resident_chunks": 1, "tile_split_keys": 128},
                  {"interleave": 2, "resident_chunks": 1}):
         h = hx.make_handle(b)
