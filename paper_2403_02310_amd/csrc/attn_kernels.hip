@@ -352,6 +352,8 @@ typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
 // 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
 #define SARATHI_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
+constexpr int kCarry = 3;  // output-MFMA operands read one step ahead
+
 // State a wave carries from one tile to the next in the software-pipelined chunk loop.
 template <int D>
 struct ChunkState {
@@ -360,6 +362,7 @@ struct ChunkState {
     // and fills the other); steps outside that loop keep everything in set 0.
     f32x16 s[2];          // raw scores of the tile whose softmax is due (already masked)
     bf16x8 p[2][2];       // bf16 softmax weights of the previous tile (B operands of its output MFMAs)
+    bf16x8 carry[kCarry]; // V operands of the next step's first output MFMAs, read at the end of this step
     float tmax;           // scaled maximum of the due scores over the column
     float m_ref;          // softmax reference, scaled base-2 units
     float l_run;          // this lane's share of the running sum
@@ -371,44 +374,43 @@ struct ChunkState {
 //   VALU:  P(t) = 2^(S(t)*scale - m_ref), row sums, bf16 packing; mask and maximum of S(t+1)
 // k_chunk: this lane's (swizzled) K chunk offsets; K_OFF / V_OFF: element offsets of the ring
 // slots read in this step (wave-uniform).
-// Order of the MFMAs of a step: which kind slot i issues and its index within that kind.
-// Scores come in pairs with an output MFMA between the pairs ("S S O S S O ...") while both kinds
-// last: the scores are then complete a few slots before the end of the step, so that masking and
-// the maximum of the next tile also run under MFMAs, and the output MFMAs that close the step use
-// four different accumulators in turn.
+// Order of the MFMAs of a step: which kind slot i issues and its index within that kind.  A step
+// with both kinds opens with three output MFMAs (their V operands were read at the end of the
+// previous step, so the matrix pipe has work right after the barrier, before any read of this step
+// returns), then all score MFMAs (one accumulator; the scores are complete a few slots before the
+// end of the step, so that masking and the maximum of the next tile also run under MFMAs), then the
+// remaining output MFMAs.
 struct ChunkSlot {
     bool is_score;
     int sub;
 };
 constexpr ChunkSlot chunk_slot(int i, int n_s, int n_o) {
-    int sc = 0, ou = 0;
-    for (int k = 0;; ++k) {
-        bool pick_s = false;
-        if (sc >= n_s) pick_s = false;
-        else if (ou >= n_o) pick_s = true;
-        else pick_s = k % 3 != 2;
-        if (k == i) return ChunkSlot{pick_s, pick_s ? sc : ou};
-        if (pick_s) ++sc; else ++ou;
-    }
+    const int lead = n_o < kCarry ? n_o : kCarry;
+    if (i < lead) return ChunkSlot{false, i};
+    if (i < lead + n_s) return ChunkSlot{true, i - lead};
+    return ChunkSlot{false, i - n_s};
 }
 constexpr int chunk_last_score_slot(int n_s, int n_o) {
-    int last = -1;
-    for (int i = 0; i < n_s + n_o; ++i)
-        if (chunk_slot(i, n_s, n_o).is_score) last = i;
-    return last;
+    return n_s == 0 ? -1 : (n_o < kCarry ? n_o : kCarry) + n_s - 1;
 }
 
 // PHASE >= 0: the tile's index inside the unit is PHASE modulo 4, which fixes the ring slots at
 // compile time (K_OFF_RT / V_OFF_RT are ignored and the operand reads need no address
 // arithmetic); PHASE < 0: slots given at run time.  The step reads register set PP and fills set
 // PP ^ 1 (SWAP) or set PP again (the results are copied back).
-template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT, int PHASE = -1, int PP = 0, bool SWAP = false>
+// CARRY_IN: the operands of the first kCarry output MFMAs are in st.carry (read by the previous step);
+// CARRY_OUT: this step reads them for the next step (whose previous tile, this step's current one,
+// has been in LDS and visible since this step's barrier).
+template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT, bool CARRY_IN, bool CARRY_OUT, int PHASE = -1, int PP = 0,
+          bool SWAP = false>
 __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qreg)[D / 16], const uint16_t *smem,
                                            const int (&k_chunk)[D / 16], int v_rd, int K_OFF_RT, int V_OFF_RT, float scale,
                                            int next_key0, int pos_eff) {
     constexpr int TE_ = kTileKeys * D;
+    static_assert(!CARRY_IN || HAS_PREV, "carried operands belong to output MFMAs");
     const int K_OFF = PHASE >= 0 ? ((PHASE + 1) & (kRing - 1)) * TE_ : K_OFF_RT;
     const int V_OFF = PHASE >= 0 ? ((PHASE + 3) & (kRing - 1)) * TE_ : V_OFF_RT;
+    const int V_OFF_NEXT = (V_OFF + TE_) & (kRing * TE_ - 1);  // ring slot of the current tile
     constexpr int OUT = SWAP ? (PP ^ 1) : PP;
     constexpr int NS = D / 16;
     constexpr int NB = D / 32;
@@ -428,9 +430,11 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
         // output MFMA j: page j / NB, channel block j % NB
         return smem + v_rd + (V_OFF + ((j / NB) * D + (j % NB) * 32) * 16);
     };
+    static_assert(AHEAD == kCarry, "the operands carried between steps fill the read-ahead window");
     bf16x8 frag[AHEAD + 1];
+    bf16x8 nxt[kCarry];
 #pragma unroll
-    for (int i = 0; i < AHEAD && i < NM; ++i) frag[i] = lds_bf16x8(operand(i));
+    for (int i = 0; i < AHEAD && i < NM; ++i) frag[i] = CARRY_IN ? st.carry[i] : lds_bf16x8(operand(i));
 
     f32x16 s_tmp;
     f32x16 &s_next = SWAP ? st.s[OUT] : s_tmp;
@@ -472,6 +476,8 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
     for (int i = 0; i < NM; ++i) {
         bf16x8 &ahead = frag[(i + AHEAD) % (AHEAD + 1)];
         if (i + AHEAD < NM) ahead = lds_bf16x8(operand(i + AHEAD));
+        else if (CARRY_OUT)  // operand j = i + AHEAD - NM of the next step: page j / NB, channel block j % NB of the current tile
+            nxt[i + AHEAD - NM] = lds_bf16x8(smem + v_rd + (V_OFF_NEXT + (((i + AHEAD - NM) / NB) * D + ((i + AHEAD - NM) % NB) * 32) * 16));
         const bf16x8 a = frag[i % (AHEAD + 1)];
         const int j = sub_index(i);
         if (is_score(i)) {
@@ -531,6 +537,11 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
         if (!SWAP) st.s[OUT] = s_tmp;
     }
     st.l_run += psum;
+    if (CARRY_OUT) {
+        static_assert(!CARRY_OUT || NM >= kCarry, "a step that reads ahead for the next one has at least kCarry slots");
+#pragma unroll
+        for (int j = 0; j < kCarry; ++j) st.carry[j] = nxt[j];
+    }
     typedef __attribute__((ext_vector_type(4))) uint32_t pk4;
     st.p[OUT][0] = __builtin_bit_cast(bf16x8, pk4{p_new[0], p_new[1], p_new[2], p_new[3]});
     st.p[OUT][1] = __builtin_bit_cast(bf16x8, pk4{p_new[4], p_new[5], p_new[6], p_new[7]});
@@ -654,9 +665,9 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         st.p[0][0] = st.p[0][1] = bf16x8{};
         const int key0 = tile_begin * kTileKeys + h * 8;
         if (tile_begin >= mask_from)
-            chunk_step<D, false, true, true>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
+            chunk_step<D, false, true, true, false, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
         else
-            chunk_step<D, false, true, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
+            chunk_step<D, false, true, false, false, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
         st.l_run = 0.f;  // the empty step contributed exp2(-inf) = 0 terms only
     }
 
@@ -689,9 +700,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         }
         const int next_key0 = (tile + 1) * kTileKeys + h * 8;
         constexpr int kPhase = decltype(phase)::value;
-        chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value, kPhase,
-                   decltype(pp)::value, (kPhase >= 0)>(st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE,
-                                                      ((rel + 3) & (kRing - 1)) * TE, scale, next_key0, pos_eff);
+        // every step with a predecessor finds its first V operands carried over; every step with a successor reads them
+        chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value,
+                   decltype(has_prev)::value, decltype(has_next)::value, kPhase, decltype(pp)::value, (kPhase >= 0)>(
+            st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE, ((rel + 3) & (kRing - 1)) * TE, scale, next_key0,
+            pos_eff);
     };
     using T = std::true_type;
     using F = std::false_type;
