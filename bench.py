@@ -25,8 +25,8 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the attention kernels (fetch + write), from two `rocprofv3 --pmc` runs
 # (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read on a plain copy of known size;
-# the runs and the scaling are recorded in profiles/attention_c2_mistral_hybrid.md.
-MEASURED_TRAFFIC_BYTES = {"c2": 628.1e6, "c3": 1491.3e6}
+# the runs and the scaling are recorded in profiles/ (attention_c2_mistral_hybrid.md and its siblings).
+MEASURED_TRAFFIC_BYTES = {"c2": 611.3e6, "c3": 1491.4e6, "c4": 4923.0e6, "c4_chunks": 340.2e6}
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
@@ -310,15 +310,18 @@ def main() -> int:
             "note": "attention: HIP events over the timed steps; merge (the part on the caller's stream) and "
                     "kv_append: a separate pass of up to 50 steps"}
         mfma_bound = args.workload.endswith("_chunk") or args.workload.endswith("_chunks")
+        # the launch the events bracket: one kernel holding both kinds of block when the batch has both
+        has_chunk, has_wave = info.num_tile_items > 0, info.num_items > info.num_tile_items
+        attn_kernel = ("attn_hybrid_kernel (chunk-tile and wave-tile blocks in one launch)" if has_chunk and has_wave
+                       else "attn_chunk_kernel" if has_chunk else "attn_wave_kernel")
         if mfma_bound:
             ach = alg_flops / (attn_us * 1e-6) / 1e12
-            result["roofline"] = {"bound": "mfma", "kernel": "attn_chunk_kernel", "achieved": ach,
+            result["roofline"] = {"bound": "mfma", "kernel": attn_kernel, "achieved": ach,
                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                                  "traffic": None}
+                                  "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
         else:
             ach = alg_bytes / (attn_us * 1e-6) / 1e9
-            result["roofline"] = {"bound": "hbm", "kernel": "attn_wave_kernel (+ attn_chunk_kernel co-running)",
-                                  "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            result["roofline"] = {"bound": "hbm", "kernel": attn_kernel, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                                   "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
 
     # ---- CPU baseline: the fp64 checker as it stands, on the host cores, bounded sample ----
