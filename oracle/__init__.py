@@ -46,10 +46,10 @@ def _load() -> ctypes.CDLL:
         i32p = ctypes.POINTER(ctypes.c_int32)
         i64p = ctypes.POINTER(ctypes.c_int64)
         f64p = ctypes.POINTER(ctypes.c_double)
-        lib.oracle_hybrid_attention.restype = ctypes.c_int
-        lib.oracle_hybrid_attention.argtypes = [
+        lib.oracle_hybrid_attention_window.restype = ctypes.c_int
+        lib.oracle_hybrid_attention_window.argtypes = [
             u16p, u16p, u16p, i64p, i32p, i32p, i32p,
-            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
             i32p, ctypes.c_int, f64p, ctypes.c_int]
         lib.oracle_softmax_weights.restype = ctypes.c_int
         lib.oracle_softmax_weights.argtypes = [
@@ -72,8 +72,10 @@ def max_threads() -> int:
 def hybrid_attention(q_bits: np.ndarray, k_seq_bits: np.ndarray, v_seq_bits: np.ndarray,
                      kv_start: Sequence[int], q_start: Sequence[int], q_len: Sequence[int],
                      ctx_len: Sequence[int], sm_scale: float,
-                     tokens: Optional[Sequence[int]] = None, num_threads: int = 0) -> np.ndarray:
+                     tokens: Optional[Sequence[int]] = None, num_threads: int = 0, window: int = 0) -> np.ndarray:
     """Attention of every (or the listed) batch row, all heads, in fp64.
+
+    ``window`` > 0: sliding-window attention, the query at position p sees keys p-window+1 .. p.
 
     ``q_bits [T, Hq, d]``, ``k_seq_bits / v_seq_bits [sum(ctx_len), Hkv, d]`` are bf16 bit
     patterns (uint16); sequence ``s`` owns K/V rows ``kv_start[s] .. kv_start[s]+ctx_len[s]``.
@@ -99,10 +101,10 @@ def hybrid_attention(q_bits: np.ndarray, k_seq_bits: np.ndarray, v_seq_bits: np.
         tok = np.ascontiguousarray(tokens, dtype=np.int32)
         n_rows = tok.shape[0]
     out = np.empty((n_rows, Hq, d), dtype=np.float64)
-    rc = lib.oracle_hybrid_attention(
+    rc = lib.oracle_hybrid_attention_window(
         _ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16), _ptr(v, ctypes.c_uint16),
         _ptr(kvs, ctypes.c_int64), _ptr(qs, ctypes.c_int32), _ptr(ql, ctypes.c_int32),
-        _ptr(cl, ctypes.c_int32), S, T, Hq, Hkv, d, float(sm_scale),
+        _ptr(cl, ctypes.c_int32), S, T, Hq, Hkv, d, float(sm_scale), int(window),
         _ptr(tok, ctypes.c_int32) if tok is not None else None, n_rows,
         _ptr(out, ctypes.c_double), int(num_threads))
     if rc != 0:
@@ -132,8 +134,8 @@ def softmax_weights(q_bits, k_seq_bits, kv_start, q_start, q_len, ctx_len, sm_sc
 
 
 def attention_for_batch(batch, tokens: Optional[Sequence[int]] = None, q_copy: int = 0,
-                        num_threads: int = 0, kv=None) -> np.ndarray:
+                        num_threads: int = 0, kv=None, window: int = 0) -> np.ndarray:
     """Convenience: run the checker on a ``workloads.HybridBatch`` (duck-typed, not imported)."""
     k, v = kv if kv is not None else batch.kv_concat()
     return hybrid_attention(batch.q_bits(q_copy), k, v, batch.kv_start, batch.q_start, batch.q_len,
-                            batch.ctx_len, batch.sm_scale, tokens=tokens, num_threads=num_threads)
+                            batch.ctx_len, batch.sm_scale, tokens=tokens, num_threads=num_threads, window=window)

@@ -224,6 +224,85 @@ def check_chunking_invariance(attn, prompt_len=48, chunks=(48, 16, 5, 1)):
     assert np.abs(results[0][0] - results[0][-1]).max() > 1e-3
 
 
+# ---- sliding window (Table 1 lists Mistral-7B's attention as grouped-query with a sliding window) ----
+# These take ``attn`` with a keyword ``window``: the query at position p sees keys p-window+1 .. p.
+
+def check_window_bruteforce_mpmath(attn):
+    """The windowed sum written as a direct loop over keys max(0, p-W+1) .. p in 50-digit arithmetic."""
+    mpmath.mp.dps = 50
+    Hq, Hkv, d = 4, 2, 4
+    q_len, ctx_len = [4, 1, 3], [7, 9, 3]
+    scale = 0.41
+    q, k, v, kv_start, q_start, ql, cl = _small_batch(31, Hq, Hkv, d, q_len, ctx_len)
+    qf, kf, vf = bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v)
+    G = Hq // Hkv
+    for W in (1, 2, 3, 5):
+        got = attn(q, k, v, kv_start, q_start, ql, cl, scale, window=W)
+        for s in range(len(q_len)):
+            for j in range(q_len[s]):
+                pos = ctx_len[s] - q_len[s] + j
+                t = q_start[s] + j
+                for h in range(Hq):
+                    g = h // G
+                    num = [mpmath.mpf(0)] * d
+                    den = mpmath.mpf(0)
+                    for i in range(max(0, pos - W + 1), pos + 1):
+                        dot = mpmath.mpf(0)
+                        for c in range(d):
+                            dot += mpmath.mpf(float(qf[t, h, c])) * mpmath.mpf(float(kf[kv_start[s] + i, g, c]))
+                        e = mpmath.exp(mpmath.mpf(scale) * dot)
+                        den += e
+                        for c in range(d):
+                            num[c] = num[c] + e * mpmath.mpf(float(vf[kv_start[s] + i, g, c]))
+                    want = np.array([float(x / den) for x in num])
+                    np.testing.assert_allclose(got[t, h], want, rtol=1e-13, atol=1e-14)
+
+
+def check_window_of_one_returns_own_v(attn):
+    """W = 1: the only visible key is the token itself, so the output is its own V row exactly."""
+    q, k, v, kv_start, q_start, ql, cl = _small_batch(32, 4, 2, 8, [5, 1], [9, 6])
+    got = attn(q, k, v, kv_start, q_start, ql, cl, 0.5, window=1)
+    vf = bf16_bits_to_f64(v)
+    for s in range(2):
+        for j in range(ql[s]):
+            pos = cl[s] - ql[s] + j
+            for h in range(4):
+                np.testing.assert_array_equal(got[q_start[s] + j, h], vf[kv_start[s] + pos, h // 2])
+
+
+def check_window_at_least_context_changes_nothing(attn):
+    """W >= ctx_len hides no key: bit-identical to no window; W = ctx_len - 1 differs in the last row only."""
+    q, k, v, kv_start, q_start, ql, cl = _small_batch(33, 4, 2, 8, [6, 1], [10, 7])
+    base = attn(q, k, v, kv_start, q_start, ql, cl, 0.3)
+    for W in (10, 11, 1000):
+        np.testing.assert_array_equal(attn(q, k, v, kv_start, q_start, ql, cl, 0.3, window=W), base)
+    nine = attn(q, k, v, kv_start, q_start, ql, cl, 0.3, window=9)
+    np.testing.assert_array_equal(nine[:5], base[:5])       # positions 4..8 of sequence 0 see <= 9 keys anyway
+    assert np.abs(nine[5] - base[5]).max() > 1e-6             # position 9 loses key 0
+    np.testing.assert_array_equal(nine[6], base[6])         # the decode of sequence 1 (position 6) sees 7 keys
+
+
+def check_window_equals_attention_over_cut_sequence(attn):
+    """Row p under window W = the LAST row of plain attention over the sequence cut to keys p-W+1 .. p."""
+    Hq, Hkv, d, W = 4, 2, 8, 5
+    q, k, v, kv_start, q_start, ql, cl = _small_batch(34, Hq, Hkv, d, [7], [12])
+    got = attn(q, k, v, kv_start, q_start, ql, cl, 0.45, window=W)
+    for j in range(7):
+        pos = 5 + j
+        lo = max(0, pos - W + 1)
+        n = pos - lo + 1
+        cut = attn(q[j:j + 1], k[lo:pos + 1], v[lo:pos + 1], np.array([0], np.int64), np.array([0], np.int32),
+                   np.array([1], np.int32), np.array([n], np.int32), 0.45)
+        np.testing.assert_allclose(got[j], cut[0], rtol=1e-14, atol=1e-15)
+
+
+WINDOW_CHECKS = [
+    check_window_bruteforce_mpmath,
+    check_window_of_one_returns_own_v,
+    check_window_at_least_context_changes_nothing,
+    check_window_equals_attention_over_cut_sequence,
+]
+
 ALL_CHECKS = [
     check_bruteforce_mpmath,
     check_single_key_returns_v0,

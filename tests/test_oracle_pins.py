@@ -13,6 +13,11 @@ def test_pin(check):
     check(oracle.hybrid_attention)
 
 
+@pytest.mark.parametrize("check", pin_checks.WINDOW_CHECKS, ids=lambda f: f.__name__)
+def test_window_pin(check):
+    check(oracle.hybrid_attention)
+
+
 def test_softmax_weights_sum_to_one_and_lie_in_unit_interval():
     b = wl.config1_tiny()
     q = b.q_bits(); k, v = b.kv_concat()
