@@ -102,6 +102,9 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * "resident_chunks" (one-launch mode: blocks choose between chunk and wave tiles when they start so
  * that a compute unit runs at most one chunk block while decode work remains; -1 = automatic, 0 =
  * never, 1 = always),
+ * "window" (sliding-window attention as in the paper's Table 1 for Mistral-7B: with window W > 0 the
+ * query at position p reads keys p-W+1 .. p only; 0 = every key up to p; pages in front of every
+ * window of a sequence are never dereferenced),
  * "time_kernels" (0/1/2, see sarathi_get_kernel_times).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);

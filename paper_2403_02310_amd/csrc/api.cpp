@@ -205,6 +205,11 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.tile_split_keys = value;
         return SARATHI_OK;
     }
+    if (std::strcmp(name, "window") == 0) {
+        if (value < 0 || value > INT32_MAX) return fail(h, SARATHI_EINVAL, "window must be >= 0 (0 = no sliding window)");
+        h->opt.window = value;
+        return SARATHI_OK;
+    }
     if (std::strcmp(name, "resident_chunks") == 0) {
         if (value < -1 || value > 1) return fail(h, SARATHI_EINVAL, "resident_chunks must be -1, 0 or 1");
         h->opt.resident_chunks = value;
@@ -281,7 +286,7 @@ extern "C" sarathi_status sarathi_plan_hybrid_attention(sarathi_handle *h, const
             w.seq = t.seq;
             w.col_begin = t.col_begin;
             w.n_cols = t.n_cols;
-            w.key_begin = split * t.keys_per_split;
+            w.key_begin = t.key_lo + split * t.keys_per_split;
             w.key_end = std::min(t.n_keys, w.key_begin + t.keys_per_split);
             w.part_row = t.n_splits > 1 ? t.part_row0 + split * t.n_cols : -1;
             w.kind = t.kind;
@@ -417,6 +422,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     m.sched = reinterpret_cast<int32_t *>(ws + h->ws.sched);
+    m.window = (int32_t)h->opt.window;
     // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
     // has both they run side by side: the chunk kernel is forked onto a second stream, where the
     // merge of its own split tiles follows it (hidden behind the longer wave kernel).

@@ -81,6 +81,7 @@ struct AttnParams {
     int32_t num_units;       // the rest are 16-column wave tiles (four per block)
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
     int32_t *sched;          // scheduling words of the run-time role assignment (else unused)
+    int32_t window;          // sliding window: a query at position p sees keys p-window+1 .. p; 0 = all keys up to p
 };
 
 // What one work unit (tile, split) covers.
@@ -91,7 +92,7 @@ struct UnitRange {
 };
 __device__ __forceinline__ UnitRange unit_range(const TileDesc &t, int split) {
     UnitRange r;
-    r.key_begin = split * t.keys_per_split;
+    r.key_begin = t.key_lo + split * t.keys_per_split;
     r.key_end = min(t.n_keys, r.key_begin + t.keys_per_split);
     r.part_row = t.n_splits > 1 ? t.part_row0 + split * t.n_cols : -1;
     return r;
@@ -154,7 +155,7 @@ struct SoftmaxState {
 
 template <int D>
 __device__ __forceinline__ void compute_tile(TileRegs<D> &r, const bf16x8 (&qreg)[D / 32], SoftmaxState<D> &st,
-                                             int tile, int g, int pos_eff, int min_pos_eff, int ctx,
+                                             int tile, int g, int pos_eff, int min_pos_eff, int lo, int max_lo, int ctx,
                                              float scale_log2) {
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -172,6 +173,10 @@ __device__ __forceinline__ void compute_tile(TileRegs<D> &r, const bf16x8 (&qreg
     if (tile * kTileKeys + (kTileKeys - 1) > min_pos_eff) {  // wave-uniform: some lane must mask
 #pragma unroll
         for (int j = 0; j < 8; ++j) t[j] = (key0 + j <= pos_eff) ? t[j] : -INFINITY;
+    }
+    if (tile * kTileKeys < max_lo) {  // wave-uniform: some lane's sliding window starts inside or after this tile
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = (key0 + j >= lo) ? t[j] : -INFINITY;
     }
     if (tile * kTileKeys + kTileKeys > ctx) {  // wave-uniform: tile holds slots at or beyond ctx_len
         u32x4 keep;
@@ -225,6 +230,9 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
     const int head = kvh * G + (col - row * G);
     const int pos_eff = min(prefix + row, ur.key_end - 1);                 // last key this column may see here
     const int min_pos_eff = min(prefix + it.col_begin / G, ur.key_end - 1);  // the same for the tile's first column
+    // first key inside this column's sliding window, and the largest such key over the tile's columns
+    const int lo = p.window > 0 ? max(0, prefix + row - p.window + 1) : 0;
+    const int max_lo = p.window > 0 ? max(0, prefix + (it.col_begin + it.n_cols - 1) / G - p.window + 1) : 0;
 
     bf16x8 qreg[D / 32];
     {
@@ -262,11 +270,11 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
     int tile = tile_begin;
     for (; tile + 1 < tile_end; tile += 2) {
         load_tile<D>(ge, tile + 1, rb);
-        compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, ctx, p.scale_log2);
+        compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
         if (tile + 2 < tile_end) load_tile<D>(ge, tile + 2, ra);
-        compute_tile<D>(rb, qreg, st, tile + 1, g, pos_eff, min_pos_eff, ctx, p.scale_log2);
+        compute_tile<D>(rb, qreg, st, tile + 1, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
     }
-    if (tile < tile_end) compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, ctx, p.scale_log2);
+    if (tile < tile_end) compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
 
     float l = st.l + __shfl_xor(st.l, 16);
     l += __shfl_xor(l, 32);
@@ -405,7 +413,7 @@ template <int D, bool HAS_PREV, bool HAS_NEXT, bool MASK_NEXT, bool CARRY_IN, bo
           bool SWAP = false>
 __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qreg)[D / 16], const uint16_t *smem,
                                            const int (&k_chunk)[D / 16], int v_rd, int K_OFF_RT, int V_OFF_RT, float scale,
-                                           int next_key0, int pos_eff) {
+                                           int next_key0, int pos_eff, int lo) {
     constexpr int TE_ = kTileKeys * D;
     static_assert(!CARRY_IN || HAS_PREV, "carried operands belong to output MFMAs");
     const int K_OFF = PHASE >= 0 ? ((PHASE + 1) & (kRing - 1)) * TE_ : K_OFF_RT;
@@ -459,7 +467,10 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
     };
     // mask + running maximum of register r of the next tile (key next_key0 + 16*(r/8) + r%8)
     auto next_max = [&](int r) {
-        if (MASK_NEXT) s_next[r] = (next_key0 + (r >> 3) * 16 + (r & 7) <= pos_eff) ? s_next[r] : -INFINITY;
+        if (MASK_NEXT) {  // causal bound and, under a sliding window, the column's first visible key
+            const int key = next_key0 + (r >> 3) * 16 + (r & 7);
+            s_next[r] = (key <= pos_eff && key >= lo) ? s_next[r] : -INFINITY;
+        }
         smax = fmaxf(smax, s_next[r]);
     };
     constexpr int LAST_SCORE = chunk_last_score_slot(N_S, N_O);  // slot of the last score MFMA
@@ -578,6 +589,11 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     const int pos_eff = min(prefix + row, ur.key_end - 1);
     const int wave_first_col = it.col_begin + ((wave * 32 < it.n_cols) ? wave * 32 : 0);
     const int min_pos_eff = min(prefix + wave_first_col / G, ur.key_end - 1);  // wave-uniform
+    // Sliding window: first key this column sees, and the largest such key over the wave's valid
+    // columns (wave-uniform; a wave without valid columns shadows the tile's first column).
+    const int wave_last_col = it.col_begin + ((wave * 32 < it.n_cols) ? min(wave * 32 + 31, it.n_cols - 1) : 0);
+    const int lo = p.window > 0 ? max(0, prefix + row - p.window + 1) : 0;
+    const int max_lo = p.window > 0 ? max(0, prefix + wave_last_col / G - p.window + 1) : 0;
 
     bf16x8 qreg[NS];  // B operand of the score MFMAs: column n, channels 16s + 8h ..
     {
@@ -650,6 +666,8 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     const float scale = p.scale_log2;
     // first tile of the range in which some column of this wave needs masking (wave-uniform)
     const int mask_from = max(tile_begin, min(tile_end, (min_pos_eff + 1) / kTileKeys));
+    // tiles below this index hold keys in front of some column's sliding window (wave-uniform; = tile_begin without one)
+    const int mask_until = max(tile_begin, min(tile_end, (max_lo + kTileKeys - 1) / kTileKeys));
 
     // Prologue: the first tiles start loading; when they have landed the scores of tile 0 are
     // formed (as the "next" tile of an otherwise empty step).
@@ -664,10 +682,10 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         for (int r = 0; r < 16; ++r) st.s[0][r] = -INFINITY;  // "current" tile of the empty step: weights 0
         st.p[0][0] = st.p[0][1] = bf16x8{};
         const int key0 = tile_begin * kTileKeys + h * 8;
-        if (tile_begin >= mask_from)
-            chunk_step<D, false, true, true, false, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
+        if (tile_begin >= mask_from || tile_begin < mask_until)
+            chunk_step<D, false, true, true, false, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff, lo);
         else
-            chunk_step<D, false, true, false, false, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff);
+            chunk_step<D, false, true, false, false, false>(st, qreg, smem, k_chunk, v_rd, 0, 0, scale, key0, pos_eff, lo);
         st.l_run = 0.f;  // the empty step contributed exp2(-inf) = 0 terms only
     }
 
@@ -689,14 +707,22 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
             issue_page(tile + my_ahead, page_clamp(pg_next));
             pg_next = page_raw(tile + my_ahead + 1);  // looked at in the next step only
         }
-        // raise the softmax reference if this tile exceeds it by more than the slack (rare)
+        // Raise the softmax reference of the columns whose due tile exceeds it by more than the slack
+        // (rare).  Three things carry the old reference: the output accumulators (tiles up to t-2), the
+        // running sum (up to t-1) and the bf16 weights of tile t-1, which still wait for their output
+        // MFMAs in this step; all three are brought to the new one.  Columns that keep their
+        // reference get alpha = 1 (both half-waves of a column see the same tmax and m_ref).
         if (__any(st.tmax > st.m_ref + kRescaleSlack)) {
-            const float m_new = fmaxf(st.m_ref, st.tmax);
+            const float m_new = (st.tmax > st.m_ref + kRescaleSlack) ? st.tmax : st.m_ref;
             const float alpha = __builtin_amdgcn_exp2f(st.m_ref - m_new);
             st.l_run *= alpha;
             st.m_ref = m_new;
 #pragma unroll
             for (int c = 0; c < NB; ++c) st.oacc[c] *= alpha;
+            constexpr int kSet = decltype(pp)::value;
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                st.p[kSet][u] = __builtin_convertvector(__builtin_convertvector(st.p[kSet][u], f32x8) * alpha, bf16x8);
         }
         const int next_key0 = (tile + 1) * kTileKeys + h * 8;
         constexpr int kPhase = decltype(phase)::value;
@@ -704,7 +730,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         chunk_step<D, decltype(has_prev)::value, decltype(has_next)::value, decltype(mask_next)::value,
                    decltype(has_prev)::value, decltype(has_next)::value, kPhase, decltype(pp)::value, (kPhase >= 0)>(
             st, qreg, smem, k_chunk, v_rd, ((rel + 1) & (kRing - 1)) * TE, ((rel + 3) & (kRing - 1)) * TE, scale, next_key0,
-            pos_eff);
+            pos_eff, lo);
     };
     using T = std::true_type;
     using F = std::false_type;
@@ -717,12 +743,17 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         step(tile_begin, F{}, F{}, F{}, F{}, DYN{}, P0{});
     } else {
         // first tile: nothing to accumulate yet
-        if (tile_begin + 1 >= mask_from) step(tile_begin, F{}, T{}, T{}, T{}, DYN{}, P0{});
+        if (tile_begin + 1 >= mask_from || tile_begin + 1 < mask_until) step(tile_begin, F{}, T{}, T{}, T{}, DYN{}, P0{});
         else step(tile_begin, F{}, T{}, F{}, T{}, DYN{}, P0{});
         // steady state, unmasked tiles: groups of four steps with the ring slots and the register
         // sets compiled in (the group starts at tile index 1 modulo 4 and leaves the state in set 0),
         // then single steps up to the causal diagonal
         int tile = tile_begin + 1;
+        // tiles in front of a sliding window's start (none without a window), then single steps up to the
+        // tile index the unrolled group expects
+        for (; tile + 1 < tile_end && tile + 1 < mask_until; ++tile) step(tile, T{}, T{}, T{}, T{}, DYN{}, P0{});
+        for (; tile + 1 < tile_end && tile + 1 < mask_from && ((tile - tile_begin) & 3) != 1; ++tile)
+            step(tile, T{}, T{}, F{}, T{}, DYN{}, P0{});
         for (; tile + 4 < tile_end && tile + 4 < mask_from; tile += 4) {
             step(tile, T{}, T{}, F{}, T{}, P1{}, P0{});
             step(tile + 1, T{}, T{}, F{}, T{}, P2{}, P1{});
@@ -1085,6 +1116,7 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.num_units = m.num_units;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
     p.sched = nullptr;
+    p.window = m.window;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
     const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;

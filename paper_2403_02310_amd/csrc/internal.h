@@ -28,9 +28,10 @@ constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 3 * kSchedMaxK
 constexpr int kChunkBlocksForRoles = 256;   // one per compute unit
 
 // One tile of query columns of one sequence.  A "column" is one (query row, query head inside
-// a KV group) pair: col = row*G + head_in_group.  Its key range 0..n_keys-1 is cut into
-// n_splits pieces of keys_per_split keys (a multiple of 32; the last piece is shorter); every
-// piece is one work unit, run once per KV head.  The descriptor carries the sequence's lengths
+// a KV group) pair: col = row*G + head_in_group.  Its key range key_lo..n_keys-1 (key_lo = 0
+// without a sliding window, else a multiple of 32 at or below the first key its first row sees) is
+// cut into n_splits pieces of keys_per_split keys (a multiple of 32; the last piece is shorter);
+// every piece is one work unit, run once per KV head.  The descriptor carries the sequence's lengths
 // so that a unit needs no further lookups.
 struct TileDesc {
     int32_t seq;
@@ -41,7 +42,7 @@ struct TileDesc {
     int32_t keys_per_split;
     int32_t n_splits;
     int32_t part_row0;    // first partial row of split 0 (split i uses part_row0 + i*n_cols ..), -1 if n_splits == 1
-    int32_t reserved;
+    int32_t key_lo;
     int32_t q_start;
     int32_t q_len;
     int32_t ctx_len;
@@ -88,6 +89,7 @@ struct Options {
     int64_t plan_at_append = 1;     // sarathi_kv_append also plans and uploads the attention metadata of its batch
     int64_t interleave = 2;         // batches with both kinds of tile: 0 = two launches in sequence, 1 = chunk kernel on a
                                     // second stream next to the wave kernel, 2 = one launch holding both kinds of block
+    int64_t window = 0;             // sliding-window attention: a query sees its last `window` keys (itself included); 0 = all
     int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
                                     // a compute unit holds at most one chunk block while decode work remains
                                     // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)
@@ -140,6 +142,7 @@ struct AttnMeta {
     float *part_ml;              // dev
     float *part_o;               // dev
     int32_t *sched;              // dev, kSchedBytes
+    int32_t window;              // sliding window in keys, 0 = none
 };
 
 // which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch,

@@ -90,7 +90,7 @@ sarathi_status validate_batch(const sarathi_config &cfg, const int32_t *q_start,
 namespace {
 
 inline int32_t steps_of_split(const TileDesc &t, int32_t split) {
-    const int32_t b = split * t.keys_per_split;
+    const int32_t b = t.key_lo + split * t.keys_per_split;
     const int32_t e = std::min(t.n_keys, b + t.keys_per_split);
     return (int32_t)ceil_div(e - b, kTileKeys);
 }
@@ -103,9 +103,10 @@ void emit_units(Plan &plan, size_t first, size_t last, int64_t split_keys, std::
     int32_t max_steps = 0;
     for (size_t ti = first; ti < last; ++ti) {
         TileDesc &t = plan.tiles[ti];
-        int32_t ns = (t.n_keys <= split_keys + split_keys / 2) ? 1 : (int32_t)ceil_div(t.n_keys, split_keys);
-        t.keys_per_split = (int32_t)(ceil_div(ceil_div(t.n_keys, ns), kTileKeys) * kTileKeys);
-        t.n_splits = (int32_t)ceil_div(t.n_keys, t.keys_per_split);
+        const int64_t span = t.n_keys - t.key_lo;  // keys the tile reads
+        int32_t ns = (span <= split_keys + split_keys / 2) ? 1 : (int32_t)ceil_div(span, split_keys);
+        t.keys_per_split = (int32_t)(ceil_div(ceil_div(span, ns), kTileKeys) * kTileKeys);
+        t.n_splits = (int32_t)ceil_div(span, t.keys_per_split);
         if (t.n_splits > 1) {
             t.part_row0 = plan.num_part_rows;
             plan.num_part_rows += t.n_splits * t.n_cols;
@@ -136,8 +137,9 @@ void count_splits(const Plan &plan, size_t first, size_t last, int64_t split_key
                   int64_t &rows, int64_t &n_split_tiles) {
     for (size_t ti = first; ti < last; ++ti) {
         const TileDesc &t = plan.tiles[ti];
-        if (t.n_keys <= split_keys + split_keys / 2) continue;
-        const int64_t ns = ceil_div(t.n_keys, split_keys);
+        const int64_t span = t.n_keys - t.key_lo;
+        if (span <= split_keys + split_keys / 2) continue;
+        const int64_t ns = ceil_div(span, split_keys);
         n_split_units += ns;
         rows += ns * t.n_cols;
         n_split_tiles++;
@@ -175,12 +177,16 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
                 t.col_begin = (int32_t)c0;
                 t.n_cols = (int32_t)std::min<int64_t>(width, n_cols - c0);
                 t.kind = kind;
-                t.n_keys = prefix + (int32_t)((c0 + t.n_cols - 1) / G) + 1;  // keys 0 .. position of the tile's last row
+                t.n_keys = prefix + (int32_t)((c0 + t.n_cols - 1) / G) + 1;  // keys .. position of the tile's last row
+                if (opt.window > 0) {  // the first row's window starts the range (rounded down to a 32-key tile)
+                    const int64_t first_key = (int64_t)prefix + c0 / G - opt.window + 1;
+                    t.key_lo = first_key > 0 ? (int32_t)(first_key / kTileKeys * kTileKeys) : 0;
+                }
                 t.q_start = q_start[s];
                 t.q_len = q_len[s];
                 t.ctx_len = ctx_len[s];
                 plan.tiles.push_back(t);
-                keys_of_kind[kind] += t.n_keys;
+                keys_of_kind[kind] += t.n_keys - t.key_lo;
             }
         }
         if (pass == 0) n_chunk_tiles = plan.tiles.size();
@@ -226,7 +232,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         bool fits = n_split_units <= kMaxSplitUnits && rows <= ws.max_part_rows && n_split_tiles <= kMaxSplitUnits / 2 &&
                     (int64_t)plan.tiles.size() + n_split_units <= ws.max_units;
         for (const TileDesc &t : plan.tiles)
-            if (ceil_div(t.n_keys, t.kind == kKindTile ? tile_split : wave_split) > max_splits_per_tile) { fits = false; break; }
+            if (ceil_div(t.n_keys - t.key_lo, t.kind == kKindTile ? tile_split : wave_split) > max_splits_per_tile) { fits = false; break; }
         if (fits) break;
         wave_split *= 2;
         tile_split *= 2;
@@ -240,7 +246,8 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     plan.num_tile_units = (int32_t)plan.units.size();
     plan.num_tile_reduce_units = (int32_t)plan.reduce_units.size();
     plan.tile_unit_steps = 0;
-    for (size_t ti = 0; ti < n_chunk_tiles; ++ti) plan.tile_unit_steps += ceil_div(plan.tiles[ti].n_keys, kTileKeys) + plan.tiles[ti].n_splits - 1;
+    for (size_t ti = 0; ti < n_chunk_tiles; ++ti)
+        plan.tile_unit_steps += ceil_div(plan.tiles[ti].n_keys - plan.tiles[ti].key_lo, kTileKeys) + plan.tiles[ti].n_splits - 1;
     plan.wave_keys = keys_of_kind[kKindWave];
     emit_units(plan, n_chunk_tiles, plan.tiles.size(), wave_split, scratch, bucket);
 }

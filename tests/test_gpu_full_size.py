@@ -24,7 +24,7 @@ def hx():
     return harness
 
 
-def oracle_rows(batch, kv_host, q_bits, tokens):
+def oracle_rows(batch, kv_host, q_bits, tokens, window=0):
     """fp64 rows for the listed batch tokens, touching only the sequences that own them."""
     tokens = np.asarray(sorted(set(int(t) for t in tokens)), dtype=np.int64)
     qs = batch.q_start
@@ -38,7 +38,7 @@ def oracle_rows(batch, kv_host, q_bits, tokens):
     sub_qs = np.concatenate([[0], np.cumsum(q_len)[:-1]]).astype(np.int32)
     kv_start = np.concatenate([[0], np.cumsum(ctx.astype(np.int64))[:-1]])
     sub_tokens = [int(sub_qs[remap[int(s)]] + (t - qs[int(s)])) for t, s in zip(tokens, owner)]
-    ref = oracle.hybrid_attention(sub_q, k, v, kv_start, sub_qs, q_len, ctx, batch.sm_scale, tokens=sub_tokens)
+    ref = oracle.hybrid_attention(sub_q, k, v, kv_start, sub_qs, q_len, ctx, batch.sm_scale, tokens=sub_tokens, window=window)
     return tokens, ref
 
 
@@ -62,13 +62,17 @@ def sample_tokens(batch, max_decodes, rng):
     return toks
 
 
-def run_and_check(hx, batch, max_decodes, seed=0):
-    print("case", batch.name, "T", batch.num_tokens, "S", batch.num_seqs, "sum ctx", int(batch.ctx_len.sum()), flush=True)
-    st = hx.setup_and_run(batch, poison=None)
+def run_and_check(hx, batch, max_decodes, seed=0, window=0):
+    print("case", batch.name, "T", batch.num_tokens, "S", batch.num_seqs, "sum ctx", int(batch.ctx_len.sum()), "window", window, flush=True)
+    handle = None
+    if window:
+        handle = hx.make_handle(batch)
+        handle.set_option("window", window)
+    st = hx.setup_and_run(batch, poison=None, handle=handle)
     got = hx.bf16_tensor_to_f64(st["out"])
     rng = np.random.default_rng([seed, 0x5A])
     toks = sample_tokens(batch, max_decodes, rng)
-    tokens, ref = oracle_rows(batch, st["kv_host"], batch.q_bits(0), toks)
+    tokens, ref = oracle_rows(batch, st["kv_host"], batch.q_bits(0), toks, window)
     res = compare(got[tokens], ref, batch.name)
     print("   rows checked %d: max abs %.3e max row rel %.3e" % (len(tokens), res[0], res[1]), flush=True)
     return st
@@ -98,6 +102,20 @@ def test_config3_decode_only_scattered_pool(hx):
     assert int(batch.block_table.max()) > 0.9 * batch.num_pages      # pages really span the pool
     st = run_and_check(hx, batch, max_decodes=256)
     del st
+    torch.cuda.empty_cache()
+
+
+def test_config2_mistral_hybrid_sliding_window(hx):
+    """The Mistral-shape hybrid batch under sliding windows of 4096 (Mistral's own: contexts reach 4096, so only the
+    longest rows lose keys), 1024 and 100 keys."""
+    for window in (4096, 1024, 100):
+        run_and_check(hx, wl.decodes_first(wl.config2_mistral_hybrid()), max_decodes=64, window=window)
+
+
+def test_config4_yi_long_sliding_window(hx):
+    """Long contexts (to 16384) under a 4096-key window: chunks and decodes start their key ranges mid-sequence,
+    with the run-time role assignment of the hybrid launch."""
+    run_and_check(hx, wl.decodes_first(wl.config4_yi_long()), max_decodes=128, window=4096)
     torch.cuda.empty_cache()
 
 

@@ -121,6 +121,52 @@ def test_chunk_tiles_with_forced_splits_and_both_paths(hx, shape):
         compare(out, ref, str(opts))
 
 
+@pytest.mark.parametrize("shape", ["gqa4_d128", "gqa7_d128", "mqa4_d64"])
+@pytest.mark.parametrize("window", [1, 17, 64, 300])
+def test_sliding_window(hx, shape, window):
+    """Sliding-window attention (the query at p sees keys p-window+1 .. p): chunks whose rows start their
+    windows at different keys, decodes, a window longer than some contexts; default plan, forced small
+    splits, everything through chunk tiles and everything through wave tiles."""
+    s = SHAPES[shape]
+    b = wl._make("window_" + shape, s, [300, 1, 37, 1, 1, 70], [1300, 555, 37, 1, 2000, 70], 84)
+    ref = oracle.attention_for_batch(b, window=window)
+    for opts in ({}, {"tile_split_keys": 64, "split_keys": 32}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20},
+                 {"resident_chunks": 1, "tile_split_keys": 96}):
+        h = hx.make_handle(b)
+        h.set_option("window", window)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        print("window", window, "options", opts, flush=True)
+        out = hx.bf16_tensor_to_f64(hx.setup_and_run(b, 0x7FC1, handle=h)["out"])
+        compare(out, ref, "window %d %s" % (window, opts))
+
+
+def test_window_longer_than_every_context_changes_nothing(hx):
+    s = SHAPES["gqa4_d128"]
+    b = wl._make("window_inactive", s, [200, 1, 1], [700, 300, 1], 85)
+    base = hx.setup_and_run(b, 0x7FC1)["out"]
+    h = hx.make_handle(b)
+    h.set_option("window", 700)
+    out = hx.setup_and_run(b, 0x7FC1, handle=h)["out"]
+    assert torch.equal(out.view(torch.int16), base.view(torch.int16))
+
+
+@pytest.mark.parametrize("shape", ["gqa4_d128", "mqa4_d64"])
+def test_peaky_scores_raise_the_softmax_reference_mid_sequence(hx, shape):
+    """sm_scale = 1 makes scores ~ N(0, d): tile maxima jump by far more than the kernels' lazy-rescale slack,
+    so the running reference is raised again and again in mid-sequence (chunk tiles: while the weights of the
+    previous tile still wait for their output MFMAs)."""
+    s = SHAPES[shape]
+    b = wl._make("peaky_" + shape, s, [260, 1, 1, 40], [1500, 900, 33, 40], 86, sm_scale=1.0)
+    _check_batch(hx, b, check_pools=False)
+    for opts in ({"tile_split_keys": 96, "split_keys": 64}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20}):
+        h = hx.make_handle(b)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        out = hx.bf16_tensor_to_f64(hx.setup_and_run(b, 0x7FC1, handle=h)["out"])
+        compare(out, oracle.attention_for_batch(b), "peaky %s" % opts)
+
+
 def test_run_time_roles_repeat_on_one_workspace(hx):
     """Blocks that pick chunk or wave tiles when they start (per-unit flags and queue heads in the workspace):
     several launches in a row on one handle and workspace, each against the checker and equal bit for bit."""

@@ -100,7 +100,9 @@ def _coverage_check(batch, **options):
     for (seq, c0, nc), pieces in covered.items():
         prefix = int(batch.ctx_len[seq] - batch.q_len[seq])
         pieces.sort()
-        assert pieces[0][0] == 0 and pieces[-1][1] == prefix + (c0 + nc - 1) // G + 1
+        window = int(options.get("window", 0))
+        first_visible = max(0, prefix + c0 // G - window + 1) if window else 0   # first key of the tile's first row
+        assert pieces[0][0] == first_visible // 32 * 32 and pieces[-1][1] == prefix + (c0 + nc - 1) // G + 1
         for a, b in zip(pieces, pieces[1:]):
             assert a[1] == b[0]
         assert all((p[2] >= 0) == (len(pieces) > 1) for p in pieces)
@@ -117,6 +119,15 @@ def test_plan_coverage_with_forced_options():
     _coverage_check(b, split_keys=32, tile_split_keys=32)
     _coverage_check(b, tile_min_cols=1)
     _coverage_check(b, tile_min_cols=1 << 20, split_keys=1 << 20)
+
+
+@pytest.mark.parametrize("window", [1, 33, 500, 4096])
+def test_plan_coverage_under_a_sliding_window(window):
+    """Pieces start at the 32-key tile that holds the first key of the tile's first row's window."""
+    b = wl.random_hybrid(4, wl.AttnShape(14, 2, 128), n_chunks=3, n_decodes=9, max_chunk=200, max_ctx=3000)
+    _coverage_check(b, window=window)
+    _coverage_check(b, window=window, split_keys=32, tile_split_keys=64)
+    _coverage_check(wl.config4_yi_long(), window=window)
 
 
 def test_plan_stays_within_the_workspace_when_everything_is_long():
