@@ -131,15 +131,19 @@ def run_iteration(handle, batch: HybridBatch, k_cache, v_cache, bt_dev, q_dev, k
     return out_dev
 
 
-def setup_and_run(batch: HybridBatch, poison: Optional[int] = POISON_NAN, handle=None, q_copy: int = 0):
-    """Full flow on fresh pools: poison, fill prefixes, run the iteration.  Returns a dict of device state."""
+def setup_and_run(batch: HybridBatch, poison: Optional[int] = POISON_NAN, handle=None, q_copy: int = 0,
+                  kv_host: Optional[dict] = None, q_bits: Optional[np.ndarray] = None):
+    """Full flow on fresh pools: poison, fill prefixes, run the iteration.  Returns a dict of device state.
+
+    ``kv_host`` ({sequence: (k_bits, v_bits)}) and ``q_bits`` replace the batch's own seeded draws
+    (tests with hand-made values)."""
     handle = handle or make_handle(batch)
     k_cache, v_cache = make_pools(batch, poison)
     bt_dev = torch.from_numpy(batch.block_table).cuda()
-    kv_host: dict = {}
+    kv_host = {} if kv_host is None else kv_host
     fill_prefixes(handle, batch, k_cache, v_cache, bt_dev, kv_host)
     k_new, v_new = new_token_kv(batch, kv_host)
-    q_dev = bits_to_device(batch.q_bits(q_copy))
+    q_dev = bits_to_device(batch.q_bits(q_copy) if q_bits is None else q_bits)
     out = run_iteration(handle, batch, k_cache, v_cache, bt_dev, q_dev, bits_to_device(k_new), bits_to_device(v_new))
     torch.cuda.synchronize()
     return {"handle": handle, "k_cache": k_cache, "v_cache": v_cache, "bt": bt_dev, "q": q_dev, "out": out,

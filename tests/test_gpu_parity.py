@@ -167,6 +167,58 @@ def test_peaky_scores_raise_the_softmax_reference_mid_sequence(hx, shape):
         compare(out, oracle.attention_for_batch(b), "peaky %s" % opts)
 
 
+def _crafted(case, batch, rng):
+    """Hand-made Q/K/V (float64, later rounded to bf16) for one value pattern; direction u carries the scores."""
+    s = batch.shape
+    T, d = batch.num_tokens, s.head_dim
+    u = np.zeros(d); u[0] = 1.0
+    q = 0.05 * rng.standard_normal((T, s.num_q_heads, d))
+    kv = {}
+    for i in range(batch.num_seqs):
+        n = int(batch.ctx_len[i])
+        k = 0.05 * rng.standard_normal((n, s.num_kv_heads, d))
+        v = rng.standard_normal((n, s.num_kv_heads, d))
+        pos = np.arange(n)[:, None, None]
+        if case == "ascending":      # score grows ~0.5 per key: every 32-key tile lifts the maximum by ~23 (base 2)
+            k = k + 0.5 * pos * u
+        elif case == "descending":   # the first keys dominate, later weights underflow
+            k = k - 0.5 * pos * u
+        elif case == "spike_at_tile_edges":
+            k = k + 40.0 * np.isin(pos, [0, 31, 32, 33, n // 2, n - 2]) * u
+        elif case == "v_outliers":
+            v = v * np.where(rng.random((n, 1, 1)) < 0.02, 4.0, 1.0)   # larger values would break the absolute bound in bf16 output
+        elif case == "huge_equal_scores":   # large |k| orthogonal noise, identical score contribution
+            k = 0.0 * k + 30.0 * u
+        kv[i] = (k, v)
+    if case in ("ascending", "descending", "spike_at_tile_edges", "huge_equal_scores"):
+        q = q + 1.0 * u
+    if case == "zero_query":
+        q = 0.0 * q
+    return q, kv
+
+
+@pytest.mark.parametrize("case", ["ascending", "descending", "spike_at_tile_edges", "v_outliers", "huge_equal_scores", "zero_query"])
+def test_crafted_value_patterns(hx, case):
+    """Value patterns that N(0,1) draws never produce: maxima that rise or fall along the sequence, spikes on tile
+    edges, outliers in V, huge equal scores, all-equal scores; chunk tiles, wave tiles and forced splits."""
+    s = SHAPES["gqa4_d128"]
+    b = wl._make("crafted_" + case, s, [200, 1, 1, 70], [900, 1500, 40, 70], 87, sm_scale=1.0)
+    rng = np.random.default_rng([88, len(case)])
+    q, kv = _crafted(case, b, rng)
+    q_bits = wl.f32_to_bf16_bits(q.astype(np.float32))
+    kv_bits = {i: (wl.f32_to_bf16_bits(k.astype(np.float32)), wl.f32_to_bf16_bits(v.astype(np.float32))) for i, (k, v) in kv.items()}
+    k_all = np.concatenate([kv_bits[i][0] for i in range(b.num_seqs)]); v_all = np.concatenate([kv_bits[i][1] for i in range(b.num_seqs)])
+    ref = oracle.hybrid_attention(q_bits, k_all, v_all, b.kv_start, b.q_start, b.q_len, b.ctx_len, b.sm_scale)
+    assert np.isfinite(ref).all()
+    for opts in ({}, {"tile_split_keys": 96, "split_keys": 64}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20}):
+        h = hx.make_handle(b)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        print("case", case, "options", opts, flush=True)
+        st = hx.setup_and_run(b, 0x7FC1, handle=h, kv_host=dict(kv_bits), q_bits=q_bits)
+        compare(hx.bf16_tensor_to_f64(st["out"]), ref, "%s %s" % (case, opts))
+
+
 def test_run_time_roles_repeat_on_one_workspace(hx):
     """Blocks that pick chunk or wave tiles when they start (per-unit flags and queue heads in the workspace):
     several launches in a row on one handle and workspace, each against the checker and equal bit for bit."""
