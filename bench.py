@@ -157,14 +157,41 @@ def run_serving(args) -> int:
     return 0
 
 
+def run_token_budget(args) -> int:
+    """One-time profile of section 4.3: iteration time (KV append + attention only: a proxy) against the token
+    budget, at the Mistral-7B attention shape with 64 running decodes, and the chunk sizes around a query-tile edge."""
+    from paper_2403_02310_amd import token_budget as tb, workloads as wl
+    seed = 41 if args.seed is None else args.seed
+    rng = np.random.default_rng([seed, 0x7B])
+    decode_ctx = rng.integers(256, 4096 + 1, size=64).tolist()
+    timer = tb.gpu_timer({k: int(v) for k, v in (kv.split("=") for kv in args.opt)}, reps=max(5, min(args.steps, 30)))
+    rows = tb.profile(timer, wl.MISTRAL_7B, [64, 128, 256, 512, 1024, 2048, 4096], decode_ctx, chunk_prefix=2048, seed=seed)
+    targets = [150e-6, 200e-6, 300e-6, 500e-6]
+    picks = {"%d us" % round(t * 1e6): tb.compute_token_budget(rows, t) for t in targets}
+    quant = tb.tile_quantization_probe(timer, wl.MISTRAL_7B, prefix=2048, chunks=(223, 224, 225, 255, 256, 257, 288), seed=seed)
+    t512 = [r for r in rows if r["token_budget"] == 512][0]["seconds"]
+    print(json.dumps({
+        "metric": "token-budget profile (KV append + attention only): tokens/s of the budget-512 batch",
+        "value": 512 / t512, "unit": "tokens/s", "n_gpus": 1, "steps": max(5, min(args.steps, 30)), "warmup": 3,
+        "ms_per_step": t512 * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "budget: Mistral-7B attention shape, 64 decodes ctx U[256,4096] + one chunk of (budget - 64) tokens "
+                               "@prefix 2048", "seed": seed},
+        "profile_us": {str(r["token_budget"]): r["seconds"] * 1e6 for r in rows},
+        "largest_budget_within": picks,
+        "tile_quantization_us": {str(r["chunk"]): r["seconds"] * 1e6 for r in quant}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2",
-                    help="c2 (default), c3, c4, c5, <cN>_chunks, <cN>_decodes, or c5_sweep (one 8192-token prompt "
-                         "prefilled in chunks of 64 ... 2048 and in one shot)")
+                    help="c2 (default), c3, c4, c5, <cN>_chunks, <cN>_decodes, c5_sweep (one 8192-token prompt prefilled in "
+                         "chunks of 64 ... 2048 and in one shot), serve (serving loop over a request trace), budget "
+                         "(token-budget profile)")
     ap.add_argument("--seed", type=int, default=None, help="seed of the workload recipe (default: the recipe's own)")
     ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -187,6 +214,8 @@ def main() -> int:
         return run_sweep(args, binding, harness, torch)
     if args.workload == "serve":
         return run_serving(args)
+    if args.workload == "budget":
+        return run_token_budget(args)
     batch, desc = make_workload(args.workload, args.seed)
     s = batch.shape
     T, S = batch.num_tokens, batch.num_seqs
