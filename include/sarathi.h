@@ -90,9 +90,10 @@ size_t sarathi_workspace_bytes(const sarathi_handle *handle);
 /* Text of the last error on this handle (includes hipGetErrorString where relevant). */
 const char *sarathi_last_error(const sarathi_handle *handle);
 
-/* Tuning knobs, all optional: "split_keys" (target keys per split-KV work item of the
- * 16-column wave tiles, multiple of 32, 0 = automatic), "target_items" (items the automatic
- * choice aims for), "tile_split_keys" (keys per split of the 128-column chunk tiles, 0 =
+/* Tuning knobs, all optional: "split_keys" (target keys per WAVEFRONT of a 16-column wave-tile
+ * work item; an item is one block whose four wavefronts quarter its keys and merge in LDS, so it
+ * covers four times as many; multiple of 32, 0 = automatic), "target_items" (wavefronts of
+ * wave-tile work per KV head the automatic choice aims for), "tile_split_keys" (keys per split of the 128-column chunk tiles, 0 =
  * automatic), "tile_min_cols" (sequences with at least this many columns q_len*G use chunk
  * tiles), "plan_at_append" (0/1: sarathi_kv_append also plans and uploads the attention
  * metadata of its batch so that the following attention call needs no copy of its own),

@@ -78,7 +78,7 @@ struct AttnParams {
     int32_t num_kv_heads;
     int32_t group;
     int32_t num_tile_units;  // units [0, num_tile_units) are 128-column chunk tiles (one block each)
-    int32_t num_units;       // the rest are 16-column wave tiles (four per block)
+    int32_t num_units;       // the rest are 16-column wave tiles (one block each as well)
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
     int32_t *sched;          // scheduling words of the run-time role assignment (else unused)
     int32_t window;          // sliding window: a query at position p sees keys p-window+1 .. p; 0 = all keys up to p
@@ -211,9 +211,23 @@ __device__ __forceinline__ void compute_tile(TileRegs<D> &r, const bf16x8 (&qreg
         st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.v[c], pT, st.o[c], 0, 0, 0);
 }
 
+// LDS a wave-tile block needs to merge its four wavefronts: per wave 16 columns x (D + 4) floats of
+// unnormalised output (the pad spreads the columns over the banks) and 16 x (maximum, sum).
 template <int D>
-__device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc &it, int split, int kvh) {
+struct WaveMergeSmem {
+    static constexpr int kColStride = D + 4;
+    static constexpr int kOutFloats = 4 * kWaveCols * kColStride;
+    static constexpr int kTotalFloats = kOutFloats + 4 * kWaveCols * 2;
+};
+
+// One wave-tile unit = one block.  The unit's key range is quartered (in multiples of 32 keys) among
+// the block's four wavefronts, which run the same loop as independent split-KV pieces and then merge
+// their (maximum, sum, unnormalised output) through LDS in wavefront order: the block writes the final
+// rows, or one set of partial rows if the tile is split further across blocks.
+template <int D>
+__device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc &it, int split, int kvh, float *merge_lds) {
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15;
     const int g = lane >> 4;
     const int seq = it.seq;
@@ -221,7 +235,14 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
     const int q_start = it.q_start;
     const int prefix = ctx - it.q_len;
     const int G = p.group;
-    const UnitRange ur = unit_range(it, split);
+    UnitRange ur = unit_range(it, split);
+    {   // this wavefront's quarter of the unit (possibly empty: then it contributes weight zero)
+        const int quarter = ((ur.key_end - ur.key_begin + 3) / 4 + kTileKeys - 1) / kTileKeys * kTileKeys;
+        const int b = ur.key_begin + wave * quarter;   // a multiple of 32, as every piece start
+        ur.key_end = min(ur.key_end, b + quarter);
+        ur.key_begin = min(b, ur.key_end);
+    }
+    const bool piece_empty = ur.key_begin >= ur.key_end;
 
     // Lanes beyond the tile's valid columns shadow column 0 of the tile and store nothing.
     const bool col_valid = n < it.n_cols;
@@ -262,7 +283,7 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
     st.l = 0.f;
 
     const int tile_begin = ur.key_begin / kTileKeys;
-    const int tile_end = (ur.key_end + kTileKeys - 1) / kTileKeys;
+    const int tile_end = piece_empty ? tile_begin : (ur.key_end + kTileKeys - 1) / kTileKeys;
 
     // Two register sets, ping-pong: the loads of tile i+1 are in flight while tile i computes.
     TileRegs<D> ra, rb;
@@ -278,27 +299,69 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
 
     float l = st.l + __shfl_xor(st.l, 16);
     l += __shfl_xor(l, 32);
-    uint16_t *op = p.out + ((int64_t)(q_start + row) * p.num_q_heads + head) * D + g * 4;
-    if (ur.part_row < 0) {
-        if (!col_valid) return;
-        const float inv = 1.0f / l;
+
+    // Publish this wavefront's piece: lane (n, g) holds channels 16c + 4g + i of column n.
+    using MS = WaveMergeSmem<D>;
+    {
+        float *o_w = merge_lds + (wave * kWaveCols + n) * MS::kColStride + g * 4;
 #pragma unroll
-        for (int c = 0; c < D / 16; ++c) {
-            const bf16x4 o4 = __builtin_convertvector(st.o[c] * inv, bf16x4);
-            *reinterpret_cast<u32x2 *>(op + c * 16) = __builtin_bit_cast(u32x2, o4);
+        for (int c = 0; c < D / 16; ++c) *reinterpret_cast<f32x4 *>(o_w + c * 16) = st.o[c];
+        if (g == 0) {
+            float *ml = merge_lds + MS::kOutFloats + (wave * kWaveCols + n) * 2;
+            ml[0] = st.m;
+            ml[1] = l;
+        }
+    }
+    __syncthreads();
+    // Merge: thread t owns column t / 16 and D / 16 consecutive channels of it.
+    constexpr int CH = D / 16;
+    const int mc = threadIdx.x >> 4;
+    const int ch0 = (threadIdx.x & 15) * CH;
+    if (mc >= it.n_cols) return;
+    float m_w[4], m_max = kNegSentinel;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        m_w[w] = merge_lds[MS::kOutFloats + (w * kWaveCols + mc) * 2];
+        m_max = fmaxf(m_max, m_w[w]);
+    }
+    float acc[CH];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) acc[j] = 0.f;
+    float l_tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float wt = __builtin_amdgcn_exp2f(m_w[w] - m_max);
+        l_tot += wt * merge_lds[MS::kOutFloats + (w * kWaveCols + mc) * 2 + 1];
+        const float *o_w = merge_lds + (w * kWaveCols + mc) * MS::kColStride + ch0;
+#pragma unroll
+        for (int j = 0; j < CH; j += 4) {
+            const f32x4 o4 = *reinterpret_cast<const f32x4 *>(o_w + j);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[j + i] += wt * o4[i];
+        }
+    }
+    const int mcol = it.col_begin + mc;
+    const int mrow = mcol / G;
+    const int mhead = kvh * G + (mcol - mrow * G);
+    const UnitRange whole = unit_range(it, split);
+    if (whole.part_row < 0) {
+        const float inv = 1.0f / l_tot;
+        uint16_t *op = p.out + ((int64_t)(q_start + mrow) * p.num_q_heads + mhead) * D + ch0;
+#pragma unroll
+        for (int j = 0; j < CH; j += 4) {
+            const f32x4 o = {acc[j] * inv, acc[j + 1] * inv, acc[j + 2] * inv, acc[j + 3] * inv};
+            *reinterpret_cast<u32x2 *>(op + j) = __builtin_bit_cast(u32x2, __builtin_convertvector(o, bf16x4));
         }
         return;
     }
-    // Split tile: publish this piece's (reference maximum, sum, unnormalised output).
-    if (col_valid) {
-        const int64_t prow = ((int64_t)(ur.part_row + n) * p.num_kv_heads + kvh);
-        float *po = p.part_o + prow * D + g * 4;
+    // Tile split across blocks: this block's (reference maximum, sum, unnormalised output).
+    const int64_t prow = ((int64_t)(whole.part_row + mc) * p.num_kv_heads + kvh);
+    float *po = p.part_o + prow * D + ch0;
 #pragma unroll
-        for (int c = 0; c < D / 16; ++c) *reinterpret_cast<f32x4 *>(po + c * 16) = st.o[c];
-        if (g == 0) {
-            p.part_ml[prow * 2 + 0] = st.m;
-            p.part_ml[prow * 2 + 1] = l;
-        }
+    for (int j = 0; j < CH; j += 4) *reinterpret_cast<f32x4 *>(po + j) = f32x4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
+    if ((threadIdx.x & 15) == 0) {
+        p.part_ml[prow * 2 + 0] = m_max;
+        p.part_ml[prow * 2 + 1] = l_tot;
     }
 }
 
@@ -839,17 +902,15 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(AttnParams p) {
     chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
 }
 
-// Wave tiles (decodes, tiny chunks): four independent units per block, two blocks per SIMD set.
+// Wave tiles (decodes, tiny chunks): one unit per block, its keys quartered among the four wavefronts.
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
+    __shared__ __attribute__((aligned(16))) float merge_lds[WaveMergeSmem<D>::kTotalFloats];
     const int kvh = blockIdx.x % p.num_kv_heads;
     const int blk = blockIdx.x / p.num_kv_heads;
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
-    const int idx = p.num_tile_units + blk * 4 + (threadIdx.x >> 6);
-    if (idx < p.num_units) {
-        const uint32_t u = p.units[idx];
-        wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
-    }
+    const uint32_t u = p.units[p.num_tile_units + blk];
+    wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, merge_lds);
 }
 
 // Both kinds of unit in ONE launch (saves the second stream's fork and join).
@@ -872,7 +933,7 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     const int kvh = blockIdx.x % p.num_kv_heads;
     int blk = blockIdx.x / p.num_kv_heads;
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
-    const int n_wave_blocks = (p.num_units - p.num_tile_units + 3) / 4;
+    const int n_wave_blocks = p.num_units - p.num_tile_units;
     bool chunk_role = blk < p.num_tile_units;
     __shared__ int32_t role[4];  // kind, index, "this block set its compute unit's flag", "last block of its KV head to take an item"
     // compute unit, shader array and shader engine ids (bits 8..15 of HW_ID) and the XCC id
@@ -912,11 +973,10 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
             const uint32_t u = p.units[blk];
             chunk_tile_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, smem);
         } else {
-            const int idx = p.num_tile_units + (blk - p.num_tile_units) * 4 + (threadIdx.x >> 6);
-            if (idx < p.num_units) {
-                const uint32_t u = p.units[idx];
-                wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh);
-            }
+            static_assert(sizeof(float) * WaveMergeSmem<D>::kTotalFloats <= sizeof(uint16_t) * ChunkSmem<D>::kTotalElems,
+                          "the wave blocks' merge buffer lives in the chunk blocks' LDS");
+            const uint32_t u = p.units[blk];
+            wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, reinterpret_cast<float *>(smem));
         }
     }
     if (ROLES && threadIdx.x == 0) {
@@ -1119,7 +1179,7 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.window = m.window;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
-    const unsigned wave_blocks = (unsigned)((m.num_units - m.num_tile_units + 3) / 4) * (unsigned)cfg.num_kv_heads;
+    const unsigned wave_blocks = (unsigned)(m.num_units - m.num_tile_units) * (unsigned)cfg.num_kv_heads;
     if (which == 4 || which == 5) {
         p.sched = m.sched;
         const dim3 grid(chunk_blocks + wave_blocks);

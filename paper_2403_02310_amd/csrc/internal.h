@@ -55,7 +55,8 @@ inline uint32_t pack_unit(uint32_t tile, uint32_t split) { return (split << kUni
 
 struct Plan {
     std::vector<TileDesc> tiles;
-    std::vector<uint32_t> units;      // chunk-tile units first (num_tile_units), then wave-tile units; longest first in each group
+    std::vector<uint32_t> units;      // chunk-tile units first (num_tile_units), then wave-tile units; longest first in each group;
+                                      // every unit is one block per KV head (a wave-tile block quarters its keys among its wavefronts)
     int32_t num_tile_units = 0;
     std::vector<uint32_t> reduce_units;  // (8-column group, tile) of every split tile, for the merge kernel; chunk tiles first
     int32_t num_tile_reduce_units = 0;   // how many of them belong to chunk tiles
@@ -82,8 +83,8 @@ struct WorkspaceLayout {
 };
 
 struct Options {
-    int64_t split_keys = 0;         // 0 = automatic
-    int64_t target_items = 1536;    // automatic choice aims for about this many wave units per KV head
+    int64_t split_keys = 0;         // keys per wavefront of a wave-tile block (a block covers four times as many); 0 = automatic
+    int64_t target_items = 1536;    // automatic choice aims for about this many wavefronts of wave-tile work per KV head
     int64_t tile_split_keys = 0;    // keys per split of the 128-column chunk tiles, 0 = automatic
     int64_t tile_min_cols = 64;     // sequences with fewer columns (q_len*G) use wave tiles only
     int64_t plan_at_append = 1;     // sarathi_kv_append also plans and uploads the attention metadata of its batch

@@ -23,7 +23,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 constexpr int32_t kMaxSplitUnits = 8192;
 constexpr int32_t kMaxPartRows = 32768;
-constexpr int32_t kMinSplitKeys = 512;
+constexpr int32_t kMinWaveKeys = 1024;   // automatic choice: keys per wavefront of a wave-tile block before the tile is split
 constexpr int32_t kMinTileSplitKeys = 1024;
 
 WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
@@ -198,10 +198,11 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         int64_t k = forced > 0 ? forced : std::max<int64_t>(floor_keys, ceil_div(total, std::max<int64_t>(1, target)));
         return ceil_div(k, kTileKeys) * kTileKeys;
     };
-    // Wave tiles that share the chip with chunk tiles are cut finer: the two kernels compete for
-    // block slots and shorter units interleave better (measured on the Mistral-shape hybrid batch).
-    const int64_t wave_floor = n_chunk_tiles > 0 ? (kMinSplitKeys * 3) / 4 : kMinSplitKeys;
-    int64_t wave_split = pick(opt.split_keys, keys_of_kind[kKindWave], opt.target_items, wave_floor);
+    // A wave-tile unit is a BLOCK: its four wavefronts take a quarter of the unit's keys each and
+    // merge their results in LDS, so a unit of up to 4 x 1024 keys (6144 with the 1.5x allowance
+    // below) needs no partial rows and no merge kernel; "split_keys" counts keys per wavefront.
+    const int64_t wave_floor = 4 * kMinWaveKeys;
+    int64_t wave_split = pick(4 * opt.split_keys, keys_of_kind[kKindWave], std::max<int64_t>(1, opt.target_items / 4), wave_floor);
     // Chunk tiles: enough units per KV head to put two blocks on every compute unit (a block
     // alone on its unit cannot hide its per-step latencies), but never pieces below the floor.
     // Next to wave tiles the chunk blocks run in the shadow of the memory-bound ones, which keep
@@ -237,7 +238,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         wave_split *= 2;
         tile_split *= 2;
     }
-    plan.split_keys = (int32_t)std::min<int64_t>(wave_split, INT32_MAX);
+    plan.split_keys = (int32_t)std::min<int64_t>(wave_split / 4, INT32_MAX);  // per wavefront
     plan.tile_split_keys = (int32_t)std::min<int64_t>(tile_split, INT32_MAX);
 
     static thread_local std::vector<uint32_t> scratch;

@@ -82,19 +82,24 @@ def test_edge_lengths(hx):
 
 
 def test_long_decode_uses_splits_and_matches(hx):
-    """A decode long enough to be split, next to short ones; forced small split size too."""
+    """Decodes of very different lengths: by default each is one block whose four wavefronts quarter the keys and
+    merge in LDS; a decode beyond 6144 keys, and any decode under a forced small split size, is also split across
+    blocks (partial rows + merge kernel)."""
     s = wl.AttnShape(8, 2, 128)
-    b = wl._make("long_decode", s, [1, 1, 1, 5], [3000, 40, 777, 1500], 78)
+    b = wl._make("long_decode", s, [1, 1, 1, 5, 1], [3000, 40, 777, 1500, 7000], 78)
     st, got, ref, _ = _check_batch(hx, b, check_pools=False)
-    info, _ = st["handle"].plan(b.q_start, b.q_len, b.ctx_len)
-    assert info.num_reduce_items > 0
+    info, items = st["handle"].plan(b.q_start, b.q_len, b.ctx_len)
+    assert info.num_reduce_items == 1                     # only the 7000-key decode
+    assert sum(1 for it in items if it.seq == 0) == 1     # the 3000-key decode: one block, no partial rows
     h2 = hx.make_handle(b)
     h2.set_option("split_keys", 64)
     st2 = hx.setup_and_run(b, 0x7FC1, handle=h2)
+    info2, _ = h2.plan(b.q_start, b.q_len, b.ctx_len)
+    assert info2.num_reduce_items >= 4
     got2 = hx.bf16_tensor_to_f64(st2["out"])
     compare(got2, ref, "split64")
     h3 = hx.make_handle(b)
-    h3.set_option("split_keys", 1 << 20)   # never split
+    h3.set_option("split_keys", 1 << 20)   # never split across blocks
     st3 = hx.setup_and_run(b, 0x7FC1, handle=h3)
     compare(hx.bf16_tensor_to_f64(st3["out"]), ref, "nosplit")
 
