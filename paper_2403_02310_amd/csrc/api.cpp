@@ -310,20 +310,18 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     int slot;
     if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
 
-    // Metadata: q_start | prefix | per-block owner of the block's first token.
-    int32_t *host = static_cast<int32_t *>(h->staging[slot]);
+    // Metadata: one record per cache page that this iteration writes into.
+    AppendUnit *units = static_cast<AppendUnit *>(h->staging[slot]);
     const size_t n = (size_t)num_seqs;
-    std::memcpy(host, q_start, sizeof(int32_t) * n);
-    for (size_t i = 0; i < n; ++i) host[n + i] = ctx_len[i] - q_len[i];
-    int32_t *hint = host + 2 * n;
-    const int64_t n_blocks = append_blocks(h->cfg, num_tokens);
-    const int64_t threads_per_token = (int64_t)h->cfg.num_kv_heads * (h->cfg.head_dim / 8);
-    for (int64_t b = 0, sq = 0; b < n_blocks; ++b) {
-        const int64_t t = b * 256 / threads_per_token;
-        while (sq + 1 < num_seqs && q_start[sq + 1] <= t) ++sq;
-        hint[b] = (int32_t)sq;
+    size_t n_units = 0;
+    for (int32_t i = 0; i < num_seqs; ++i) {
+        const int32_t prefix = ctx_len[i] - q_len[i];
+        for (int32_t pg = prefix / kPageSize; pg <= (ctx_len[i] - 1) / kPageSize; ++pg) {
+            const int32_t first = std::max(prefix, pg * kPageSize), end = std::min(ctx_len[i], (pg + 1) * kPageSize);
+            units[n_units++] = AppendUnit{i, pg, q_start[i] + (first - prefix), (first - pg * kPageSize) | ((end - pg * kPageSize) << 8)};
+        }
     }
-    size_t used = sizeof(int32_t) * (2 * n + (size_t)n_blocks);
+    size_t used = sizeof(AppendUnit) * n_units;
     if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
     // The attention call of this iteration will get the same description: plan it now and let
     // its metadata ride along in this copy (one host-to-device copy per iteration instead of two).
@@ -333,7 +331,7 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
         const AttnMetaOffsets o = attn_meta_offsets(h->plan);
         const size_t attn_off = align_up(used, 256);
         if (attn_off + o.total <= h->staging_bytes) {
-            pack_attn_meta(reinterpret_cast<char *>(host) + attn_off, h->plan, o);
+            pack_attn_meta(reinterpret_cast<char *>(units) + attn_off, h->plan, o);
             used = attn_off + o.total;
             h->resident_attn_off = attn_off;
             h->resident_desc.resize(2 * n);
@@ -347,20 +345,17 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
 
     char *dev = static_cast<char *>(workspace) + h->ws.meta;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(dev, host, used, hipMemcpyHostToDevice, s);
+    hipError_t e = hipMemcpyAsync(dev, units, used, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "hipMemcpyAsync(metadata)", e); }
     e = hipEventRecord(h->staged[slot], s);
     if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
     h->in_flight[slot] = true;
 
     AppendMeta m;
-    m.q_start = reinterpret_cast<const int32_t *>(dev);
-    m.prefix = m.q_start + n;
-    m.block_hint = m.prefix + n;
+    m.units = reinterpret_cast<const AppendUnit *>(dev);
     m.block_table = block_table;
     m.max_blocks = h->cfg.max_blocks_per_seq;
-    m.num_seqs = num_seqs;
-    m.num_tokens = num_tokens;
+    m.num_units = (int32_t)n_units;
     const int t0 = timing_begin(h, 0, s);
     e = (hipError_t)launch_kv_append(h->cfg, m, k_new, v_new, k_cache, v_cache, num_pages, stream);
     timing_end(h, 0, t0, s);

@@ -1048,10 +1048,14 @@ __global__ __launch_bounds__(kMergeCols * D / 4) void splitkv_reduce_kernel(Redu
 }
 
 // ---------------------------------------------------------------------------------------
-// KV append: byte copies into the paged pools.  A block moves kAppendTokensPerBlock tokens;
-// one thread-step moves 8 channels of one (token, KV head): a 16-byte K store and eight 2-byte
-// V stores (V pages are channel-major).  The host supplies, per block, the sequence that owns
-// the block's first token, so a thread finds its sequence by walking forward a few entries.
+// KV append: byte copies into the paged pools.  A block fills the slots [lo, hi) of one cache
+// page for one KV head (a page unit, built by the host: a decode has one, a chunk one per page
+// it touches), one thread per channel.  K rows go over as 16-byte pieces (a page holds them
+// slot-major, so the hi - lo rows are one contiguous run).  V pages are channel-major: thread c
+// owns the 32-byte row of channel c, gathers the tokens' values of that channel (a wavefront
+// reads 128 contiguous bytes per token) and, when the whole page is new, writes the row with
+// two 16-byte stores (the block writes the 4 KiB page front to back); a partly filled page
+// gets 2-byte stores into its new slots only, the others keep their bytes.
 // ---------------------------------------------------------------------------------------
 struct AppendParams {
     const uint16_t *k_new;
@@ -1059,40 +1063,59 @@ struct AppendParams {
     uint16_t *k_cache;
     uint16_t *v_cache;
     const int32_t *block_table;
-    const int32_t *q_start;
-    const int32_t *prefix;      // ctx_len - q_len per sequence
-    const int32_t *block_hint;  // per thread block: sequence owning the block's first token
+    const AppendUnit *units;
     int64_t num_pages;
-    int64_t total_threads;
     int32_t max_blocks;
-    int32_t num_seqs;
     int32_t num_kv_heads;
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void kv_append_kernel(AppendParams p) {
-    constexpr int kChunks = D / 8;
-    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (tid >= p.total_threads) return;
-    const int chunk = (int)(tid % kChunks);
-    const int h = (int)((tid / kChunks) % p.num_kv_heads);
-    const int t = (int)(tid / ((int64_t)kChunks * p.num_kv_heads));
-    int s = p.block_hint[blockIdx.x];
-    while (s + 1 < p.num_seqs && p.q_start[s + 1] <= t) ++s;  // a block spans few tokens: few steps
-    const int pos = p.prefix[s] + (t - p.q_start[s]);
-    const int64_t page = p.block_table[(int64_t)s * p.max_blocks + pos / kPageSize];
+__global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
+    constexpr int kPieces = D / 8;  // 16-byte pieces of one K row
+    const int unit = (int)(blockIdx.x / (unsigned)p.num_kv_heads);
+    const int h = (int)(blockIdx.x % (unsigned)p.num_kv_heads);
+    const u32x4 rec = *reinterpret_cast<const u32x4 *>(p.units + unit);
+    const int lo = (int)(rec[3] & 0xFFu), hi = (int)(rec[3] >> 8);
+    const int n = hi - lo;
+    const int64_t page = p.block_table[(int64_t)(int)rec[0] * p.max_blocks + (int)rec[1]];
     if (page < 0 || page >= p.num_pages) return;  // a corrupt table entry must not become a wild store
-    const int slot = pos % kPageSize;
-    const int64_t src = ((int64_t)t * p.num_kv_heads + h) * D + chunk * 8;
-    const u32x4 kv = *reinterpret_cast<const u32x4 *>(p.k_new + src);
-    const u32x4 vv = *reinterpret_cast<const u32x4 *>(p.v_new + src);
+    const int64_t row_stride = (int64_t)p.num_kv_heads * D;
+    const int64_t src = ((int64_t)(int)rec[2] * p.num_kv_heads + h) * D;
     const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
-    *reinterpret_cast<u32x4 *>(p.k_cache + head_base + slot * D + chunk * 8) = kv;
-    uint16_t *vdst = p.v_cache + head_base + (int64_t)(chunk * 8) * kPageSize + slot;
+    const int tid = (int)threadIdx.x;
+
+    // V: gather first (all loads in flight before any store)
+    const uint16_t *vsrc = p.v_new + src + tid;
+    uint16_t x[kPageSize];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint32_t word = vv[e >> 1];
-        vdst[e * kPageSize] = (uint16_t)((e & 1) ? (word >> 16) : (word & 0xFFFFu));
+    for (int i = 0; i < kPageSize; ++i) x[i] = (i < n) ? vsrc[i * row_stride] : (uint16_t)0;
+
+    // K: n rows of D channels, destination contiguous
+    const uint16_t *ksrc = p.k_new + src;
+    uint16_t *kdst = p.k_cache + head_base + (int64_t)lo * D;
+#pragma unroll
+    for (int r = 0; r < (kPageSize * kPieces) / D; ++r) {
+        const int j = tid + r * D;
+        const int i = j / kPieces, piece = j % kPieces;
+        if (i < n)
+            *reinterpret_cast<u32x4 *>(kdst + i * D + piece * 8) =
+                *reinterpret_cast<const u32x4 *>(ksrc + i * row_stride + piece * 8);
+    }
+
+    uint16_t *vdst = p.v_cache + head_base + (int64_t)tid * kPageSize;
+    if (n == kPageSize) {
+        u32x4 w0, w1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            w0[e] = (uint32_t)x[2 * e] | ((uint32_t)x[2 * e + 1] << 16);
+            w1[e] = (uint32_t)x[8 + 2 * e] | ((uint32_t)x[9 + 2 * e] << 16);
+        }
+        *reinterpret_cast<u32x4 *>(vdst) = w0;
+        *reinterpret_cast<u32x4 *>(vdst + 8) = w1;
+    } else {
+#pragma unroll
+        for (int i = 0; i < kPageSize; ++i)
+            if (i < n) vdst[lo + i] = x[i];
     }
 }
 
@@ -1101,27 +1124,23 @@ __global__ __launch_bounds__(256) void kv_append_kernel(AppendParams p) {
 // ---------------------------------------------------------------------------------------
 int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void *k_new, const void *v_new,
                      void *k_cache, void *v_cache, int64_t num_pages, void *stream) {
-    if (m.num_tokens == 0) return (int)hipSuccess;
+    if (m.num_units == 0) return (int)hipSuccess;
     AppendParams p;
     p.k_new = static_cast<const uint16_t *>(k_new);
     p.v_new = static_cast<const uint16_t *>(v_new);
     p.k_cache = static_cast<uint16_t *>(k_cache);
     p.v_cache = static_cast<uint16_t *>(v_cache);
     p.block_table = m.block_table;
-    p.q_start = m.q_start;
-    p.prefix = m.prefix;
-    p.block_hint = m.block_hint;
+    p.units = m.units;
     p.num_pages = num_pages;
     p.max_blocks = m.max_blocks;
-    p.num_seqs = m.num_seqs;
     p.num_kv_heads = cfg.num_kv_heads;
-    p.total_threads = append_threads(cfg, m.num_tokens);
-    const unsigned blocks = (unsigned)append_blocks(cfg, m.num_tokens);
+    const unsigned blocks = (unsigned)m.num_units * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
-        hipLaunchKernelGGL(kv_append_kernel<128>, dim3(blocks), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(kv_append_kernel<128>, dim3(blocks), dim3(128), 0, st, p);
     else
-        hipLaunchKernelGGL(kv_append_kernel<64>, dim3(blocks), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(kv_append_kernel<64>, dim3(blocks), dim3(64), 0, st, p);
     return (int)hipGetLastError();
 }
 

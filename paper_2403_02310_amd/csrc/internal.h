@@ -109,22 +109,25 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
                     Plan &plan);
 
 // ---- device launchers (attn_kernels.hip); each returns a hipError_t cast to int ----
-// The append kernel runs one thread per 8 channels of one (token, KV head), 256 per block.
-inline int64_t append_threads(const sarathi_config &cfg, int32_t num_tokens) {
-    return (int64_t)num_tokens * cfg.num_kv_heads * (cfg.head_dim / 8);
-}
-inline int64_t append_blocks(const sarathi_config &cfg, int32_t num_tokens) {
-    return (append_threads(cfg, num_tokens) + 255) / 256;
+// The append kernel's work item is a page unit: the slots [lo, hi) of ONE cache page that this
+// iteration fills for one sequence (a decode has one unit, a chunk one per page it touches).
+struct AppendUnit {
+    int32_t seq;        // sequence index (row of the block table)
+    int32_t page_idx;   // logical page of the sequence (column of the block table)
+    int32_t row0;       // batch row of the token that goes to slot `lo`
+    int32_t lo_hi;      // lo | hi << 8, 0 <= lo < hi <= 16
+};
+static_assert(sizeof(AppendUnit) == 16, "AppendUnit is uploaded as is and read as one 16-byte word");
+// every sequence touches at most q_len/16 + 2 pages
+inline int64_t max_append_units(const sarathi_config &cfg) {
+    return (int64_t)cfg.max_tokens / kPageSize + 2 * (int64_t)cfg.max_seqs;
 }
 
 struct AppendMeta {
-    const int32_t *q_start;      // dev [S]
-    const int32_t *prefix;       // dev [S]: ctx_len - q_len
-    const int32_t *block_hint;   // dev [append_blocks]: sequence owning the block's first token
+    const AppendUnit *units;     // dev [num_units]
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
-    int32_t num_seqs;
-    int32_t num_tokens;
+    int32_t num_units;
 };
 
 int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void *k_new, const void *v_new,

@@ -39,7 +39,7 @@ WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
     w.max_reduce_units = (int32_t)std::min<int64_t>(kMaxPartRows / (2 * kReduceCols) + kMaxSplitUnits / 2, INT32_MAX / 64);
     const size_t attn_meta = sizeof(TileDesc) * (size_t)w.max_tiles +
                              sizeof(uint32_t) * ((size_t)w.max_units + (size_t)w.max_reduce_units) + 64;
-    const size_t append_meta = sizeof(int32_t) * (2 * (size_t)cfg.max_seqs + (size_t)append_blocks(cfg, cfg.max_tokens)) + 64;
+    const size_t append_meta = sizeof(AppendUnit) * (size_t)max_append_units(cfg) + 64;
     size_t off = 0;
     w.meta = off;
     w.meta_bytes = align_up(align_up(append_meta, 256) + attn_meta, 256);  // an append may carry both
