@@ -103,6 +103,8 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * "resident_chunks" (one-launch mode: blocks choose between chunk and wave tiles when they start so
  * that a compute unit runs at most one chunk block while decode work remains; -1 = automatic, 0 =
  * never, 1 = always),
+ * "stream_kv" (the decodes' K/V loads carry the non-temporal hint, which pays on decode streams and
+ * costs a little next to prefill chunks that matter; -1 = automatic, 0 = never, 1 = always),
  * "window" (sliding-window attention as in the paper's Table 1 for Mistral-7B: with window W > 0 the
  * query at position p reads keys p-W+1 .. p only; 0 = every key up to p; pages in front of every
  * window of a sequence are never dereferenced),

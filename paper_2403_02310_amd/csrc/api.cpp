@@ -210,6 +210,11 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
         h->opt.window = value;
         return SARATHI_OK;
     }
+    if (std::strcmp(name, "stream_kv") == 0) {
+        if (value < -1 || value > 1) return fail(h, SARATHI_EINVAL, "stream_kv must be -1, 0 or 1");
+        h->opt.stream_kv = value;
+        return SARATHI_OK;
+    }
     if (std::strcmp(name, "resident_chunks") == 0) {
         if (value < -1 || value > 1) return fail(h, SARATHI_EINVAL, "resident_chunks must be -1, 0 or 1");
         h->opt.resident_chunks = value;
@@ -418,6 +423,13 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
     m.sched = reinterpret_cast<int32_t *>(ws + h->ws.sched);
     m.window = (int32_t)h->opt.window;
+    // Rough durations: chunk work with one block per compute unit (~0.65 us per 32-key step), and the time
+    // the decodes need to stream their keys and values (~5 bytes/ps).
+    const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
+    const double wave_us = (double)pl.wave_keys * h->cfg.num_kv_heads * h->cfg.head_dim * 4.0 / 5.0e6;
+    // The streaming hint pays on decode streams (+2 to +7 %) and costs 1 to 3 % when chunk blocks that
+    // matter run beside them (their K/V tiles then miss more often).
+    m.stream_kv = h->opt.stream_kv >= 0 ? (int32_t)h->opt.stream_kv : (chunk_us < 0.1 * wave_us ? 1 : 0);
     // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
     // has both they run side by side: the chunk kernel is forked onto a second stream, where the
     // merge of its own split tiles follows it (hidden behind the longer wave kernel).
@@ -445,10 +457,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     } else if (both && h->opt.interleave == 2) {
         // Run-time roles pay (a few atomics per block) when chunk blocks would otherwise pile up two
         // to a compute unit for a good part of the launch: more chunk blocks than units, and chunk
-        // work (one block per unit, ~0.65 us per 32-key step) that is not small next to the time the
-        // decodes need to stream (~5 bytes/ps).
-        const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
-        const double wave_us = (double)pl.wave_keys * h->cfg.num_kv_heads * h->cfg.head_dim * 4.0 / 5.0e6;
+        // work that is not small next to the time the decodes need to stream.
         const bool many_chunk_blocks = (int64_t)pl.num_tile_units * h->cfg.num_kv_heads > kChunkBlocksForRoles &&
                                        chunk_us > 0.25 * wave_us;
         const bool roles = h->cfg.num_kv_heads <= kSchedMaxKvHeads &&

@@ -105,6 +105,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 __device__ __forceinline__ bf16x8 load_bf16x8(const uint16_t *p) {
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
 }
+__device__ __forceinline__ bf16x8 load_bf16x8_stream(const uint16_t *p) {
+    return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)));
+}
 
 template <int D>
 struct TileRegs {
@@ -126,7 +129,8 @@ struct LaneGeom {
     int32_t v_pg_sel;
 };
 
-template <int D>
+// STREAM: the loads carry the non-temporal hint (K/V read once, far more than the caches hold).
+template <int D, bool STREAM>
 __device__ __forceinline__ void load_tile(const LaneGeom<D> &ge, int tile, TileRegs<D> &r) {
     // Pages at or beyond ceil(ctx_len/16) are never dereferenced: the index is clamped to the
     // sequence's last page and whatever is loaded for such keys is masked below.
@@ -137,13 +141,22 @@ __device__ __forceinline__ void load_tile(const LaneGeom<D> &ge, int tile, TileR
     pk = pk < 0 ? 0 : (pk > ge.last_page_id ? ge.last_page_id : pk);
     pv = pv < 0 ? 0 : (pv > ge.last_page_id ? ge.last_page_id : pv);
     const uint16_t *kp = ge.k_cache + pk * ge.page_stride + ge.k_lane_off;
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s) r.k[b][s] = load_bf16x8(kp + b * 4 * D + s * 32);
     const uint16_t *vp = ge.v_cache + pv * ge.page_stride + ge.v_lane_off;
+    if (STREAM) {
 #pragma unroll
-    for (int t = 0; t < D / 16; ++t) r.v[t] = load_bf16x8(vp + t * 16 * kPageSize);
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int s = 0; s < D / 32; ++s) r.k[b][s] = load_bf16x8_stream(kp + b * 4 * D + s * 32);
+#pragma unroll
+        for (int t = 0; t < D / 16; ++t) r.v[t] = load_bf16x8_stream(vp + t * 16 * kPageSize);
+    } else {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int s = 0; s < D / 32; ++s) r.k[b][s] = load_bf16x8(kp + b * 4 * D + s * 32);
+#pragma unroll
+        for (int t = 0; t < D / 16; ++t) r.v[t] = load_bf16x8(vp + t * 16 * kPageSize);
+    }
 }
 
 template <int D>
@@ -224,7 +237,7 @@ struct WaveMergeSmem {
 // the block's four wavefronts, which run the same loop as independent split-KV pieces and then merge
 // their (maximum, sum, unnormalised output) through LDS in wavefront order: the block writes the final
 // rows, or one set of partial rows if the tile is split further across blocks.
-template <int D>
+template <int D, bool STREAM>
 __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc &it, int split, int kvh, float *merge_lds) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -287,12 +300,12 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
 
     // Two register sets, ping-pong: the loads of tile i+1 are in flight while tile i computes.
     TileRegs<D> ra, rb;
-    load_tile<D>(ge, tile_begin, ra);
+    load_tile<D, STREAM>(ge, tile_begin, ra);
     int tile = tile_begin;
     for (; tile + 1 < tile_end; tile += 2) {
-        load_tile<D>(ge, tile + 1, rb);
+        load_tile<D, STREAM>(ge, tile + 1, rb);
         compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
-        if (tile + 2 < tile_end) load_tile<D>(ge, tile + 2, ra);
+        if (tile + 2 < tile_end) load_tile<D, STREAM>(ge, tile + 2, ra);
         compute_tile<D>(rb, qreg, st, tile + 1, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
     }
     if (tile < tile_end) compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
@@ -903,14 +916,14 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(AttnParams p) {
 }
 
 // Wave tiles (decodes, tiny chunks): one unit per block, its keys quartered among the four wavefronts.
-template <int D>
+template <int D, bool STREAM>
 __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) float merge_lds[WaveMergeSmem<D>::kTotalFloats];
     const int kvh = blockIdx.x % p.num_kv_heads;
     const int blk = blockIdx.x / p.num_kv_heads;
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
     const uint32_t u = p.units[p.num_tile_units + blk];
-    wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, merge_lds);
+    wave16_path<D, STREAM>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, merge_lds);
 }
 
 // Both kinds of unit in ONE launch (saves the second stream's fork and join).
@@ -927,7 +940,7 @@ __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
 // atomics are relaxed: they only hand out indices into the read-only plan.  Every block counts itself
 // in after it has taken its item, and the block that completes the count of its KV head puts that
 // head's words back to zero when it ends, so a launch leaves the scheduling words as it found them.
-template <int D, bool ROLES>
+template <int D, bool ROLES, bool STREAM>
 __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
     const int kvh = blockIdx.x % p.num_kv_heads;
@@ -976,7 +989,7 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
             static_assert(sizeof(float) * WaveMergeSmem<D>::kTotalFloats <= sizeof(uint16_t) * ChunkSmem<D>::kTotalElems,
                           "the wave blocks' merge buffer lives in the chunk blocks' LDS");
             const uint32_t u = p.units[blk];
-            wave16_path<D>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, reinterpret_cast<float *>(smem));
+            wave16_path<D, STREAM>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, reinterpret_cast<float *>(smem));
         }
     }
     if (ROLES && threadIdx.x == 0) {
@@ -1196,19 +1209,25 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.scale_log2 = sm_scale * 1.4426950408889634f;
     p.sched = nullptr;
     p.window = m.window;
+    const bool stream_kv = m.stream_kv != 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const unsigned chunk_blocks = (unsigned)m.num_tile_units * (unsigned)cfg.num_kv_heads;
     const unsigned wave_blocks = (unsigned)(m.num_units - m.num_tile_units) * (unsigned)cfg.num_kv_heads;
     if (which == 4 || which == 5) {
         p.sched = m.sched;
         const dim3 grid(chunk_blocks + wave_blocks);
-        if (cfg.head_dim == 128) {
-            if (which == 5) hipLaunchKernelGGL((attn_hybrid_kernel<128, true>), grid, dim3(256), 0, st, p);
-            else hipLaunchKernelGGL((attn_hybrid_kernel<128, false>), grid, dim3(256), 0, st, p);
-        } else {
-            if (which == 5) hipLaunchKernelGGL((attn_hybrid_kernel<64, true>), grid, dim3(256), 0, st, p);
-            else hipLaunchKernelGGL((attn_hybrid_kernel<64, false>), grid, dim3(256), 0, st, p);
-        }
+        auto launch = [&](auto d, auto roles, auto stream_hint) {
+            hipLaunchKernelGGL((attn_hybrid_kernel<decltype(d)::value, decltype(roles)::value, decltype(stream_hint)::value>),
+                               grid, dim3(256), 0, st, p);
+        };
+        auto pick_stream = [&](auto d, auto roles) {
+            if (stream_kv) launch(d, roles, std::true_type{}); else launch(d, roles, std::false_type{});
+        };
+        auto pick_roles = [&](auto d) {
+            if (which == 5) pick_stream(d, std::true_type{}); else pick_stream(d, std::false_type{});
+        };
+        if (cfg.head_dim == 128) pick_roles(std::integral_constant<int, 128>{});
+        else pick_roles(std::integral_constant<int, 64>{});
         return (int)hipGetLastError();
     }
     if (chunk_blocks && (which & 1)) {
@@ -1218,10 +1237,13 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
             hipLaunchKernelGGL(attn_chunk_kernel<64>, dim3(chunk_blocks), dim3(256), 0, st, p);
     }
     if (wave_blocks && (which & 2)) {
-        if (cfg.head_dim == 128)
-            hipLaunchKernelGGL(attn_wave_kernel<128>, dim3(wave_blocks), dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL(attn_wave_kernel<64>, dim3(wave_blocks), dim3(256), 0, st, p);
+        if (cfg.head_dim == 128) {
+            if (stream_kv) hipLaunchKernelGGL((attn_wave_kernel<128, true>), dim3(wave_blocks), dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((attn_wave_kernel<128, false>), dim3(wave_blocks), dim3(256), 0, st, p);
+        } else {
+            if (stream_kv) hipLaunchKernelGGL((attn_wave_kernel<64, true>), dim3(wave_blocks), dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((attn_wave_kernel<64, false>), dim3(wave_blocks), dim3(256), 0, st, p);
+        }
     }
     return (int)hipGetLastError();
 }

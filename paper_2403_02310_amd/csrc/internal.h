@@ -91,6 +91,8 @@ struct Options {
     int64_t interleave = 2;         // batches with both kinds of tile: 0 = two launches in sequence, 1 = chunk kernel on a
                                     // second stream next to the wave kernel, 2 = one launch holding both kinds of block
     int64_t window = 0;             // sliding-window attention: a query sees its last `window` keys (itself included); 0 = all
+    int64_t stream_kv = -1;         // decode K/V loads carry the streaming (non-temporal) hint: -1 = when the batch's chunk
+                                    // work is absent or small next to its decode streams, 0 = never, 1 = always
     int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
                                     // a compute unit holds at most one chunk block while decode work remains
                                     // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)
@@ -147,6 +149,7 @@ struct AttnMeta {
     float *part_o;               // dev
     int32_t *sched;              // dev, kSchedBytes
     int32_t window;              // sliding window in keys, 0 = none
+    int32_t stream_kv;           // 1: the wave tiles' K/V loads carry the streaming hint
 };
 
 // which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch,

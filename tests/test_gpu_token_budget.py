@@ -11,9 +11,10 @@ pytestmark = pytest.mark.gpu
 
 def test_profile_and_pick():
     shape = wl.AttnShape(8, 2, 128)
-    timer = tb.gpu_timer(reps=7, warmup=2)
+    timer = tb.gpu_timer(reps=15, warmup=3)
     rows = tb.profile(timer, shape, [64, 512, 2048], [700] * 8, chunk_prefix=1500, seed=3)
     print(rows, flush=True)
     assert rows[0]["seconds"] < rows[2]["seconds"]                      # 56 vs 2040 chunk rows on a 1500-token prefix
     pick = tb.compute_token_budget(rows, rows[1]["seconds"] * 1.05)
-    assert pick in (512, 2048) and tb.compute_token_budget(rows, rows[0]["seconds"] * 0.5) is None
+    assert pick in (512, 2048)
+    assert tb.compute_token_budget(rows, min(r["seconds"] for r in rows) * 0.5) is None   # a target nothing meets
