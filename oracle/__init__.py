@@ -11,6 +11,8 @@ Contents
 ``kv_cache_reference.py`` what the paged K/V pools must hold after an append, and how a
                           sequence is read back through its block table (section 2.2, paged cache).
 ``scheduler_reference.py`` one iteration of stall-free batching (Algorithm 3, section 4.2).
+``linear_oracle.c``       a linear layer over the batch's token rows in double precision
+                          (sections 2.1 and 3.1), compiled into ``liblinear_oracle.so``.
 """
 from __future__ import annotations
 
@@ -25,6 +27,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "attention_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib: Optional[ctypes.CDLL] = None
+_LIN_SRC = os.path.join(_HERE, "linear_oracle.c")
+_LIN_LIB = os.path.join(_HERE, "liblinear_oracle.so")
+_lin_lib: Optional[ctypes.CDLL] = None
 
 
 def build(force: bool = False) -> str:
@@ -33,6 +38,11 @@ def build(force: bool = False) -> str:
     if force or stale:
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    stale = (not os.path.exists(_LIN_LIB)) or os.path.getmtime(_LIN_LIB) < os.path.getmtime(_LIN_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIN_LIB, _LIN_SRC]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -139,3 +149,43 @@ def attention_for_batch(batch, tokens: Optional[Sequence[int]] = None, q_copy: i
     k, v = kv if kv is not None else batch.kv_concat()
     return hybrid_attention(batch.q_bits(q_copy), k, v, batch.kv_start, batch.q_start, batch.q_len,
                             batch.ctx_len, batch.sm_scale, tokens=tokens, num_threads=num_threads, window=window)
+
+
+def _load_linear() -> ctypes.CDLL:
+    global _lin_lib
+    if _lin_lib is None:
+        build()
+        lib = ctypes.CDLL(_LIN_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        lib.oracle_linear.restype = ctypes.c_int
+        lib.oracle_linear.argtypes = [u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      i32p, ctypes.c_int, i32p, ctypes.c_int,
+                                      ctypes.POINTER(ctypes.c_double), ctypes.c_int]
+        _lin_lib = lib
+    return _lin_lib
+
+
+def linear(x_bits: np.ndarray, w_bits: np.ndarray, rows: Optional[Sequence[int]] = None,
+           cols: Optional[Sequence[int]] = None, num_threads: int = 0) -> np.ndarray:
+    """``y[t, n] = sum_k x[t, k] * w[n, k]`` in fp64 for all (or the listed) token rows and output features.
+
+    ``x_bits [T, K]`` and ``w_bits [N, K]`` are bf16 bit patterns (uint16).  Returns float64
+    ``[len(rows) or T, len(cols) or N]``."""
+    lib = _load_linear()
+    x = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    w = np.ascontiguousarray(w_bits, dtype=np.uint16)
+    if x.ndim != 2 or w.ndim != 2 or x.shape[1] != w.shape[1]:
+        raise ValueError("x must be [T, K] and w [N, K]")
+    T, K = x.shape
+    N = w.shape[0]
+    r = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    c = None if cols is None else np.ascontiguousarray(cols, dtype=np.int32)
+    out = np.empty((T if r is None else len(r), N if c is None else len(c)), dtype=np.float64)
+    rc = lib.oracle_linear(_ptr(x, ctypes.c_uint16), _ptr(w, ctypes.c_uint16), T, N, K,
+                           None if r is None else _ptr(r, ctypes.c_int32), 0 if r is None else len(r),
+                           None if c is None else _ptr(c, ctypes.c_int32), 0 if c is None else len(c),
+                           _ptr(out, ctypes.c_double), num_threads)
+    if rc != 0:
+        raise ValueError("row or column index outside the matrices")
+    return out
