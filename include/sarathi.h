@@ -242,6 +242,29 @@ sarathi_status sarathi_build_stall_free_batch(int32_t token_budget, int32_t chun
                                               int64_t free_pages, int32_t page_size, int32_t max_batch_size,
                                               sarathi_batch *out);
 
+/* ---- Linear layers of the batch (paper sections 2.1 and 3.1) --------------------------------------
+ * The Q/K/V and output projections and the two feed-forward transformations of section 2.1 apply one
+ * weight matrix to every token of the batch; section 3.1 studies their cost as a function of the number
+ * of tokens (bound by fetching the weights while the batch is small, by arithmetic beyond a threshold).
+ *
+ *     y[t][n] = sum over k < in_features of  x[t][k] * w[n][k]        (no bias)
+ *
+ * x  device, bf16 [num_tokens, in_features], row-major (one row per token of the batch)
+ * w  device, bf16 [out_features, in_features], row-major (one row per output feature)
+ * y  device, bf16 [num_tokens, out_features], row-major; products and sums are fp32, one rounding at the end
+ * workspace  device scratch of workspace_bytes bytes, or NULL with 0: fp32 partial tiles when the k range
+ *            is cut into pieces so that a small batch still streams the weights through every compute unit;
+ *            sarathi_linear_workspace_bytes gives the size that allows every cut the planner would make;
+ *            with less (or none) the call still computes the same y with fewer pieces.
+ * Shapes: out_features a multiple of 128, in_features a multiple of 64 and at most 2^20, num_tokens >= 0
+ * (0 is a no-op), num_tokens * out_features below 2^40; anything else returns SARATHI_ESHAPE.  Null
+ * pointers with num_tokens > 0 return SARATHI_EINVAL, a failed launch SARATHI_EHIP.  The work is enqueued on
+ * `stream` and not synchronised; the caller owns all buffers and keeps them alive until the stream drains.
+ * Pieces are added in index order: the result does not depend on timing. */
+size_t sarathi_linear_workspace_bytes(int32_t num_tokens, int32_t out_features, int32_t in_features);
+sarathi_status sarathi_linear(const void *x, const void *w, void *y, int32_t num_tokens, int32_t out_features,
+                              int32_t in_features, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

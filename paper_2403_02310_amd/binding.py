@@ -63,7 +63,8 @@ class KernelTimes(ctypes.Structure):
 
 EXPORTED = ["sarathi_create", "sarathi_destroy", "sarathi_workspace_bytes", "sarathi_last_error",
             "sarathi_set_option", "sarathi_kv_append", "sarathi_hybrid_attention",
-            "sarathi_plan_hybrid_attention", "sarathi_build_stall_free_batch", "sarathi_get_kernel_times"]
+            "sarathi_plan_hybrid_attention", "sarathi_build_stall_free_batch", "sarathi_get_kernel_times",
+            "sarathi_linear", "sarathi_linear_workspace_bytes"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libsarathi.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -99,6 +100,10 @@ lib.sarathi_build_stall_free_batch.argtypes = [ctypes.c_int32, ctypes.c_int32,
                                                ctypes.POINTER(Request), ctypes.c_int32,
                                                ctypes.POINTER(Request), ctypes.c_int32,
                                                ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(Batch)]
+lib.sarathi_linear_workspace_bytes.restype = ctypes.c_size_t
+lib.sarathi_linear_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+lib.sarathi_linear.restype = ctypes.c_int
+lib.sarathi_linear.argtypes = [_vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_size_t, _vp]
 
 
 def _i32(a) -> np.ndarray:
@@ -268,3 +273,23 @@ def build_stall_free_batch(token_budget: int, chunk_size: int, running_decodes: 
             "ctx_len": ctx_len[:n].tolist(), "num_tokens": b.num_tokens, "num_decodes": b.num_decodes,
             "num_prefill_chunks": b.num_prefill_chunks, "num_admitted": b.num_admitted,
             "free_pages_left": int(b.free_pages_left)}
+
+
+def linear_workspace_bytes(num_tokens: int, out_features: int, in_features: int) -> int:
+    return int(lib.sarathi_linear_workspace_bytes(num_tokens, out_features, in_features))
+
+
+def linear(x, w, y, workspace=None, stream=None) -> None:
+    """``y[t, n] = sum_k x[t, k] * w[n, k]`` on the GPU (``sarathi_linear``): x [T, K], w [N, K], y [T, N], bf16
+    device tensors; ``workspace`` an optional device byte tensor for split-K partial tiles."""
+    T, K = x.shape
+    N = w.shape[0]
+    if w.shape[1] != K or tuple(y.shape) != (T, N):
+        raise ValueError("x [T, K], w [N, K], y [T, N] expected")
+    for t in (x, w, y):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (_dev(workspace), workspace.numel() * workspace.element_size())
+    st = lib.sarathi_linear(_dev(x), _dev(w), _dev(y), T, N, K, ws_ptr, ws_bytes, _stream(stream))
+    if st != 0:
+        raise SarathiError(st, "sarathi_linear(T=%d, N=%d, K=%d) failed" % (T, N, K))

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsarathi.so")
-SOURCES = ["api.cpp", "plan.cpp", "scheduler.cpp", "attn_kernels.hip"]
+SOURCES = ["api.cpp", "linear_api.cpp", "plan.cpp", "scheduler.cpp", "attn_kernels.hip", "linear_kernels.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

@@ -163,4 +163,16 @@ int launch_zero(void *ptr, size_t bytes, void *stream);
 
 int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream);
 
+// ---- linear layer (linear_kernels.hip) ----
+struct LinearPlan {
+    int32_t n_tiles;      // 128-feature tiles
+    int32_t t_tiles;      // 128-token tiles
+    int32_t splits;       // pieces of the k range (1 = none); pieces write fp32 partial tiles
+    int32_t k_per_split;  // multiple of 32
+};
+// Tiling of y[T, N] = x[T, K] w[N, K]^T; the k range is cut only as far as `workspace_bytes` holds the partial tiles.
+LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes);
+int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, int32_t T, int32_t N, int32_t K,
+                  void *workspace, void *stream);
+
 }  // namespace sarathi

@@ -135,3 +135,19 @@ def test_plan_stays_within_the_workspace_when_everything_is_long():
     b = wl._make("long", s, [2048], [16384], 9)
     info = _coverage_check(b, tile_split_keys=32, split_keys=32)
     assert info.num_part_rows <= 32768
+
+
+def test_linear_refuses_bad_shapes_without_a_gpu():
+    """Shape checks come before any device call, so they can be exercised here."""
+    for (T, N, K) in [(-1, 128, 64), (4, 0, 64), (4, 100, 64), (4, 128, 32), (4, 128, 96), (4, 128, (1 << 20) + 64)]:
+        assert binding.lib.sarathi_linear(None, None, None, T, N, K, None, 0, None) == binding.ESHAPE
+        assert binding.linear_workspace_bytes(T, N, K) == 0
+    assert binding.lib.sarathi_linear(None, None, None, 0, 128, 64, None, 0, None) == 0          # no tokens: nothing to do
+    assert binding.lib.sarathi_linear(None, None, None, 4, 128, 64, None, 0, None) == binding.EINVAL
+
+
+def test_linear_split_k_workspace_sizes():
+    """A small batch on big weights asks for partial tiles; a batch that fills the chip by itself asks for none."""
+    assert binding.linear_workspace_bytes(2048, 4096, 4096) == 0
+    small = binding.linear_workspace_bytes(128, 4096, 14336)
+    assert small > 0 and small % (128 * 4096 * 4) == 0 and small // (128 * 4096 * 4) <= 16
