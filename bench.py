@@ -182,6 +182,56 @@ def run_token_budget(args) -> int:
     return 0
 
 
+def run_linear(args) -> int:
+    """Linear layers of one transformer layer against the number of tokens in the batch (section 3.1): the four
+    models of Table 1, one GPU's share under the paper's tensor-parallel degree."""
+    from paper_2403_02310_amd import linear_layers as ll
+    tokens = [16, 64, 128, 256, 384, 512, 768, 1024, 1536, 2048]
+    timer = ll.gpu_timer(reps=max(5, min(args.steps, 20)))
+    out = {}
+    for key, m in ll.MODELS.items():
+        shapes = ll.layer_shapes(m)
+        rows = ll.profile(timer, shapes, tokens)
+        wb = ll.weight_bytes(shapes)
+        out[key] = {"model": m.name, "tp": m.tp, "layers": {n: [o, i] for n, o, i in shapes}, "weight_bytes": wb,
+                    "us": {str(r["tokens"]): r["seconds"] * 1e6 for r in rows},
+                    "weights_GBps": {str(r["tokens"]): wb / r["seconds"] / 1e9 for r in rows},
+                    "TFLOPs": {str(r["tokens"]): ll.flops(shapes, r["tokens"]) / r["seconds"] / 1e12 for r in rows},
+                    "per_layer_us": {str(r["tokens"]): {n: v * 1e6 for n, v in r["per_layer"].items()} for r in rows
+                                     if r["tokens"] in (16, 128, 512, 2048)},
+                    "knee_tokens": ll.knee(rows)}
+    head = out["llama2-70b"]
+    t2048 = head["us"]["2048"] * 1e-6
+    ach = head["TFLOPs"]["2048"]
+    result = {
+        "metric": "linear layers of one transformer layer, tokens/s at 2048 tokens (LLaMA2-70B, one GPU of TP4)",
+        "value": 2048 / t2048, "unit": "tokens/s", "n_gpus": 1, "steps": max(5, min(args.steps, 20)), "warmup": 3,
+        "ms_per_step": t2048 * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "linear: QKV, attention-output, feed-forward up and down projections of the four models of "
+                               "Table 1 at one GPU's tensor-parallel share, 16 ... 2048 tokens, N(0,1) values"},
+        "roofline": {"bound": "mfma", "kernel": "linear_kernel", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "small_batch_roofline": {"bound": "hbm", "tokens": 128, "achieved": head["weights_GBps"]["128"], "peak": HBM_PEAK_GBS,
+                                 "unit": "GB/s", "frac": head["weights_GBps"]["128"] / HBM_PEAK_GBS},
+        "models": out}
+    if not args.no_cpu_baseline:
+        import oracle
+        from paper_2403_02310_amd import workloads as wl
+        # the fp64 checker on a bounded sample: 64 token rows of LLaMA2-70B's feed-forward down projection
+        _, n, k = ll.layer_shapes(ll.MODELS["llama2-70b"])[3]
+        xb = wl.normal_bf16((77, 0x58), (64, k)); wb_ = wl.normal_bf16((77, 0x57), (n, k))
+        tc = time.perf_counter()
+        oracle.linear(xb, wb_)
+        dt = time.perf_counter() - tc
+        per_token = dt / 64 * (ll.flops(ll.layer_shapes(ll.MODELS["llama2-70b"]), 1) / (2.0 * n * k))
+        result["cpu_baseline"] = {"value": 1.0 / per_token, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
+                                  "seconds": dt, "sample": "64 token rows of the feed-forward down projection (8192 x 7168), "
+                                  "scaled by flops to the four layers"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -190,7 +240,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c2",
                     help="c2 (default), c3, c4, c5, <cN>_chunks, <cN>_decodes, c5_sweep (one 8192-token prompt prefilled in "
                          "chunks of 64 ... 2048 and in one shot), serve (serving loop over a request trace), budget "
-                         "(token-budget profile)")
+                         "(token-budget profile), linear (linear layers against the number of tokens)")
     ap.add_argument("--seed", type=int, default=None, help="seed of the workload recipe (default: the recipe's own)")
     ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -215,6 +265,8 @@ def main() -> int:
         return run_serving(args)
     if args.workload == "budget":
         return run_token_budget(args)
+    if args.workload == "linear":
+        return run_linear(args)
     batch, desc = make_workload(args.workload, args.seed)
     s = batch.shape
     T, S = batch.num_tokens, batch.num_seqs

@@ -165,10 +165,11 @@ int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32
 
 // ---- linear layer (linear_kernels.hip) ----
 struct LinearPlan {
-    int32_t n_tiles;      // 128-feature tiles
-    int32_t t_tiles;      // 128-token tiles
+    int32_t token_tile;   // tokens per workgroup tile: 256 or 128
+    int32_t n_tiles;      // 256-feature tiles
+    int32_t t_tiles;      // token tiles
     int32_t splits;       // pieces of the k range (1 = none); pieces write fp32 partial tiles
-    int32_t k_per_split;  // multiple of 32
+    int32_t k_per_split;  // multiple of 64
 };
 // Tiling of y[T, N] = x[T, K] w[N, K]^T; the k range is cut only as far as `workspace_bytes` holds the partial tiles.
 LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes);

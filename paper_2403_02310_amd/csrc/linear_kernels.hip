@@ -5,16 +5,22 @@
 // shape of v_mfma_f32_32x32x16_bf16 (a lane holds one row and 8 consecutive k).  The weight tile
 // is the A operand (rows = output features) and the token tile the B operand (columns = tokens),
 // so an accumulator lane holds ONE token and runs of 4 consecutive features: the output row of
-// a token is written in 8-byte pieces that a wavefront's 2 x 2 accumulator tiles complete to
-// 128 contiguous bytes.
+// a token is written in 8-byte pieces that a wavefront's accumulator tiles complete to 128
+// contiguous bytes.
 //
-// Workgroup = 4 wavefronts = a 128-feature x 128-token tile, wavefront = 64 x 64 of it (2 x 2
-// MFMA tiles, 64 accumulator registers).  k advances in stages of 32: a stage is a 128 x 32
-// weight tile and a 128 x 32 token tile (8 KiB each) brought from global memory straight into
-// LDS (global_load_lds_dwordx4: no staging registers) into a ring of four stages (64 KiB, two
-// workgroups per compute unit); loads run three stages ahead, one barrier per stage.  LDS rows
-// are 64 bytes; the four 16-byte pieces of row r are XOR-swizzled with (r >> 2) & 3 so that the 16
-// lanes of a b128 operand read, which walk 16 rows at one logical piece, hit distinct banks.
+// Workgroup = 8 wavefronts = a 256-feature x BM-token tile (BM = 256, or 128 for small batches),
+// wavefront = 64 features x BM/2 tokens of it (2 x 4 or 2 x 2 MFMA tiles).  What bounds a tile
+// shape on this chip is the path global memory -> LDS (64 bytes per clock and compute unit): a
+// 128 x 128 tile needs 512 bytes of operands per MFMA, which is that path's whole bandwidth at
+// full MFMA rate (measured: 0.30 of the MFMA peak, 0.40 with half of the loads made redundant);
+// 256 x 256 needs half of it.  k advances in stages of 64, so that an LDS row is one full 128-byte
+// line of its matrix row; a stage (256 x 64 weights, BM x 64 tokens) goes from global memory
+// straight into LDS (global_load_lds_dwordx4: no staging registers) into a ring of two stages
+// (BM = 256: 128 KiB) or three (BM = 128: 144 KiB), one workgroup per compute unit, one barrier
+// per stage.  The eight 16-byte pieces of LDS row r are XOR-swizzled with (r >> 1) & 7 so that the
+// 16 lanes of a b128 operand read, which walk 16 rows at one logical piece, hit distinct banks.
+// Inside a stage the loop is skewed by one k16 step: the operands of step s+1 are read while the
+// MFMAs of step s issue, and the last step's operands are carried over the barrier.
 //
 // Few tokens (a decode-heavy batch): one token tile covers the batch, the weights are read
 // once, and the layer is bound by fetching them (section 3.1); when the grid would leave
@@ -41,25 +47,26 @@ typedef __attribute__((ext_vector_type(16))) float lf32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t lu32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t lu32x2;
 
-constexpr int kLinTile = 128;    // features and tokens per workgroup tile
-constexpr int kLinStageK = 32;   // k per stage
-constexpr int kLinRing = 4;      // stages in the LDS ring
-constexpr int kLinStageElems = 2 * kLinTile * kLinStageK;  // weight tile then token tile
+constexpr int kLinBN = 256;      // features per workgroup tile
+constexpr int kLinStageK = 64;   // k per stage: one 128-byte line of every row
 constexpr int kLinXcds = 8;
+constexpr int kLinThreads = 512;
 
 typedef void __attribute__((address_space(3))) *lin_lds_ptr;
 
 // One direct global -> LDS load of 16 bytes per lane: lane l fetches base + byte_off(l) and the
 // wavefront's kilobyte lands at LDS byte address lds_addr + 16 l.  Inline assembly so that the
 // compiler's wait-count pass does not treat later LDS operand reads as possibly overtaken by it;
-// these loads are waited for by hand (LIN_WAIT_VMCNT), the only vector-memory loads of the loop.
+// these loads are waited for by hand, they are the only vector-memory loads of the loop.
 __device__ __forceinline__ void lin_dma_load_16(const uint16_t *base, int byte_off, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_addr), "v"(byte_off), "s"(base)
                  : "memory");
 }
-#define LIN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+// s_waitcnt with the vector-memory counter at n and the LDS counter at zero (gfx9 encoding: vmcnt in bits
+// 3:0 and 15:14, expcnt 6:4 left at its maximum, lgkmcnt 11:8)
+#define LIN_WAIT_VMCNT_AND_LDS(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
 
 struct LinearParams {
     const uint16_t *x;   // [T, K]
@@ -68,11 +75,19 @@ struct LinearParams {
     float *part;         // [splits, T, N] when splits > 1
     int32_t T, N, K;
     int32_t n_tiles, t_tiles, splits;
-    int32_t k_per_split;  // multiple of 32
+    int32_t k_per_split;  // multiple of 64
 };
 
-__global__ __launch_bounds__(256, 2) void linear_kernel(LinearParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[kLinRing * kLinStageElems];
+template <int BM, int RING>
+__global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) {
+    constexpr int W_ELEMS = kLinBN * kLinStageK;
+    constexpr int X_ELEMS = BM * kLinStageK;
+    constexpr int STAGE = W_ELEMS + X_ELEMS;
+    constexpr int X_LOADS = BM / 64;            // 1 KiB loads of token rows per wavefront and stage
+    constexpr int LOADS = 4 + X_LOADS;          // all loads of a wavefront per stage
+    constexpr int NJ = BM / 64;                 // 32-token MFMA tiles per wavefront
+    constexpr int STEPS = kLinStageK / 16;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[RING * STAGE];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // work item of this workgroup
@@ -83,100 +98,126 @@ __global__ __launch_bounds__(256, 2) void linear_kernel(LinearParams p) {
     const int split = j % p.splits;
     const int n_tile = xcd + kLinXcds * (j / p.splits);
     if (n_tile >= p.n_tiles) return;
-    const int n0 = n_tile * kLinTile;
-    const int t0 = t_tile * kLinTile;
+    const int n0 = n_tile * kLinBN;
+    const int t0 = t_tile * BM;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);
     const int n_stages = (k_end - k_begin) / kLinStageK;
 
-    // ---- global -> LDS: wavefront w moves rows 32w .. 32w+31 of the weight tile and of the token tile,
-    // two loads of 16 rows each.  Lane l of a load fills physical piece l % 4 of row l / 4 and
-    // therefore fetches the logical piece that lives there.
-    int w_off[2], x_off[2];
+    // ---- global -> LDS: wavefront w moves rows 32w .. 32w+31 of the weight tile (four loads of 8 rows) and
+    // rows (BM/8)w .. of the token tile.  Lane l of a load fills physical piece l % 8 of row l / 8 and
+    // therefore fetches the logical piece that lives there.  Rows past the matrix re-read its last row.
+    int w_off[4], x_off[X_LOADS];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = wave * 32 + i * 16 + (lane >> 2);
-        const int piece = (lane & 3) ^ ((row >> 2) & 3);
-        w_off[i] = (row * p.K + piece * 8) * 2;                  // feature rows always exist (N % 128 == 0)
-        const int tok = min(t0 + row, p.T - 1) - t0;             // token rows past the batch re-read its last row
-        x_off[i] = (tok * p.K + piece * 8) * 2;
+    for (int i = 0; i < 4; ++i) {
+        const int row = wave * 32 + i * 8 + (lane >> 3);
+        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        w_off[i] = ((min(n0 + row, p.N - 1) - n0) * p.K + piece * 8) * 2;
+    }
+#pragma unroll
+    for (int i = 0; i < X_LOADS; ++i) {
+        const int row = wave * (BM / 8) + i * 8 + (lane >> 3);
+        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        x_off[i] = ((min(t0 + row, p.T - 1) - t0) * p.K + piece * 8) * 2;
     }
     const uint16_t *w_base = p.w + (int64_t)n0 * p.K + k_begin;
     const uint16_t *x_base = p.x + (int64_t)t0 * p.K + k_begin;
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(lin_lds_ptr)(smem);
-    auto issue_stage = [&](int stage) {
+    auto issue_stage = [&](int stage, int slot) {
         // stages past the range re-read the last one into a free slot: every step issues the same
         // number of loads, so one wait count serves the whole loop
         const int s = min(stage, n_stages - 1);
-        const uint32_t dst = smem_addr + (uint32_t)((stage & (kLinRing - 1)) * kLinStageElems * 2) + (uint32_t)(wave * 32 * kLinStageK * 2);
+        const uint32_t dst = smem_addr + (uint32_t)(slot * STAGE * 2);
         const uint16_t *wb = w_base + s * kLinStageK;
         const uint16_t *xb = x_base + s * kLinStageK;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            lin_dma_load_16(wb, w_off[i], dst + i * 1024);
-            lin_dma_load_16(xb, x_off[i], dst + kLinTile * kLinStageK * 2 + i * 1024);
-        }
+        for (int i = 0; i < 4; ++i) lin_dma_load_16(wb, w_off[i], dst + (uint32_t)((wave * 32 + i * 8) * kLinStageK * 2));
+#pragma unroll
+        for (int i = 0; i < X_LOADS; ++i)
+            lin_dma_load_16(xb, x_off[i], dst + (uint32_t)(W_ELEMS * 2 + (wave * (BM / 8) + i * 8) * kLinStageK * 2));
     };
 
-    // ---- operands: wavefront (wn, wt) owns features 64wn.. and tokens 64wt.. of the tile
-    const int wn = wave & 1, wt = wave >> 1;
+    // ---- operands: wavefront (wn, wt) owns features 64wn.. and tokens (BM/2)wt.. of the tile
+    const int wn = wave & 3, wt = wave >> 2;
     const int r = lane & 31, g = lane >> 5;
-    int a_off[2][2], b_off[2][2];  // [sub-tile][k16 step] element offsets inside a stage
+    int a_row[2], a_key[2], b_row[NJ], b_key[NJ];  // element offset of the row inside a stage, and its swizzle key
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+        const int ra = wn * 64 + i * 32 + r;
+        a_row[i] = ra * kLinStageK;
+        a_key[i] = (ra >> 1) & 7;
+    }
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int ra = wn * 64 + i * 32 + r;
-            const int rb = wt * 64 + i * 32 + r;
-            a_off[i][s] = ra * kLinStageK + (((2 * s + g) ^ ((ra >> 2) & 3)) * 8);
-            b_off[i][s] = kLinTile * kLinStageK + rb * kLinStageK + (((2 * s + g) ^ ((rb >> 2) & 3)) * 8);
-        }
+    for (int jj = 0; jj < NJ; ++jj) {
+        const int rb = wt * (BM / 2) + jj * 32 + r;
+        b_row[jj] = W_ELEMS + rb * kLinStageK;
+        b_key[jj] = (rb >> 1) & 7;
+    }
 
-    lf32x16 acc[2][2];
+    lf32x16 acc[2][NJ];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
+        for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][jj][e] = 0.f;
 
-    issue_stage(0);
-    issue_stage(1);
-    issue_stage(2);
-    for (int st = 0; st < n_stages; ++st) {
-        // stage st has landed when at most the loads of the two later stages are in flight; the barrier
-        // also says that every wavefront is done with the slot stage st+3 is about to overwrite
-        LIN_WAIT_VMCNT(8);
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        issue_stage(st + 3);
-        const uint16_t *sp = smem + (st & (kLinRing - 1)) * kLinStageElems;
-        lbf16x8 a[2][2], b[2][2];
+    auto read_step = [&](const uint16_t *sp, int s, lbf16x8 (&a)[2], lbf16x8 (&b)[NJ]) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int i = 0; i < 2; ++i)
+            a[i] = __builtin_bit_cast(lbf16x8, *reinterpret_cast<const lu32x4 *>(sp + a_row[i] + (((2 * s + g) ^ a_key[i]) * 8)));
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                a[i][s] = __builtin_bit_cast(lbf16x8, *reinterpret_cast<const lu32x4 *>(sp + a_off[i][s]));
-                b[i][s] = __builtin_bit_cast(lbf16x8, *reinterpret_cast<const lu32x4 *>(sp + b_off[i][s]));
-            }
+        for (int jj = 0; jj < NJ; ++jj)
+            b[jj] = __builtin_bit_cast(lbf16x8, *reinterpret_cast<const lu32x4 *>(sp + b_row[jj] + (((2 * s + g) ^ b_key[jj]) * 8)));
+    };
+    auto mfma_step = [&](const lbf16x8 (&a)[2], const lbf16x8 (&b)[NJ]) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
             for (int i = 0; i < 2; ++i)
+                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[jj], acc[i][jj], 0, 0, 0);
+    };
+    lbf16x8 fa[2][2], fb[2][NJ];  // two operand sets used in turn
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj)
-                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][s], b[jj][s], acc[i][jj], 0, 0, 0);
+    for (int i = 0; i < 2; ++i) fa[1][i] = lbf16x8{};  // the "last step of stage -1": zeros
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj) fb[1][jj] = lbf16x8{};
+
+#pragma unroll
+    for (int st = 0; st < RING - 1; ++st) issue_stage(st, st);
+    int slot = 0, fill_slot = RING - 1;
+    for (int st = 0; st < n_stages; ++st) {
+        // Stage st has landed when at most the loads of the RING-2 later stages are in flight.  The barrier
+        // also says that every wavefront has its last operands of stage st-1 in registers (LDS counter at
+        // zero), so the slot of stage st-1 may be overwritten by stage st+RING-1.
+        LIN_WAIT_VMCNT_AND_LDS((RING - 2) * LOADS);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue_stage(st + RING - 1, fill_slot);
+        const uint16_t *sp = smem + slot * STAGE;
+        // STEPS is even: step s uses operand set s & 1; set 1 arrives holding the previous stage's last step
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            read_step(sp, s, fa[s & 1], fb[s & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(fa[(s & 1) ^ 1], fb[(s & 1) ^ 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        slot = slot + 1 == RING ? 0 : slot + 1;
+        fill_slot = fill_slot + 1 == RING ? 0 : fill_slot + 1;
     }
-    LIN_WAIT_VMCNT(0);  // the padding loads past the range must land before the workgroup's LDS is given back
+    mfma_step(fa[1], fb[1]);
+    LIN_WAIT_VMCNT_AND_LDS(0);  // the padding loads past the range must land before the workgroup's LDS is given back
 
     // ---- output: accumulator element e of lane (r, g) of tile (i, jj) is feature 32i + 8(e/4) + 4g + e%4, token 32jj + r
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-        const int t = t0 + wt * 64 + jj * 32 + r;
+    for (int jj = 0; jj < NJ; ++jj) {
+        const int t = t0 + wt * (BM / 2) + jj * 32 + r;
         if (t >= p.T) continue;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int f0 = n0 + wn * 64 + i * 32 + 4 * g;
+            if (f0 >= p.N) continue;  // N is a multiple of 128, the tile 256 wide
             if (p.splits == 1) {
                 uint16_t *yp = p.y + (int64_t)t * p.N + f0;
 #pragma unroll
@@ -208,27 +249,41 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(const float *part, u
 
 LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) {
     LinearPlan pl;
-    pl.n_tiles = N / kLinTile;
-    pl.t_tiles = (T + kLinTile - 1) / kLinTile;
+    // Token tile: 256 tokens per tile halve the operand traffic per MFMA, 128 waste less of a ragged batch;
+    // the narrow tile costs about a quarter more per token.
+    const int64_t cost256 = (int64_t)((T + 255) / 256) * 256 * 4, cost128 = (int64_t)((T + 127) / 128) * 128 * 5;
+    pl.token_tile = cost128 < cost256 ? 128 : 256;
+    pl.n_tiles = (N + kLinBN - 1) / kLinBN;
+    pl.t_tiles = (T + pl.token_tile - 1) / pl.token_tile;
     pl.splits = 1;
     pl.k_per_split = K;
-    // Fewer workgroups than the chip holds at once (two per compute unit): cut k so that the
-    // weights stream through all compute units.  A piece keeps at least 8 stages (256 k).
+    // Fewer workgroups than compute units, or a ragged last round of them: cutting k into pieces fills
+    // the chip, at the price of fp32 partial tiles that are written, read back and added by a second
+    // kernel.  Rough cost of a piece count s, in microseconds: rounds of workgroups x stages per piece x
+    // the time of a stage (measured: ~1.95 us for 256 tokens, ~1.3 us for 128, where fetching the weights
+    // bounds it), plus the partial tiles at ~3 TB/s and the second launch.  Pieces keep at least 4 stages.
     const int64_t tiles = (int64_t)pl.n_tiles * pl.t_tiles;
-    const int64_t slots = 512;
-    if (tiles < slots) {
-        int64_t want = (slots + tiles - 1) / tiles;
-        const int64_t max_by_k = K / 256 > 0 ? K / 256 : 1;
-        if (want > max_by_k) want = max_by_k;
-        if (want > 16) want = 16;
-        const int64_t per_split_bytes = (int64_t)T * N * 4;
-        while (want > 1 && (size_t)(want * per_split_bytes) > workspace_bytes) --want;
-        if (want > 1) {
-            int32_t kps = (int32_t)((K + want - 1) / want);
-            kps = (kps + kLinStageK - 1) / kLinStageK * kLinStageK;
-            pl.k_per_split = kps;
-            pl.splits = (K + kps - 1) / kps;
-        }
+    const int64_t slots = 256;
+    const double stage_us = pl.token_tile == 256 ? 1.95 : 1.3;
+    const int64_t k_stages = K / kLinStageK;
+    auto cost_us = [&](int64_t s) {
+        const int64_t rounds = (tiles * s + slots - 1) / slots;
+        const double main_us = (double)rounds * (double)((k_stages + s - 1) / s) * stage_us;
+        return s == 1 ? main_us : main_us + 8.0 * (double)s * T * N / 3.0e6 + 5.0;
+    };
+    int64_t best = 1;
+    double best_cost = cost_us(1);
+    const int64_t per_split_bytes = (int64_t)T * N * 4;
+    for (int64_t s = 2; s <= 16 && s * 4 <= k_stages; ++s) {
+        if ((size_t)(s * per_split_bytes) > workspace_bytes) break;
+        const double c = cost_us(s);
+        if (c < 0.95 * best_cost) { best_cost = c; best = s; }
+    }
+    if (best > 1) {
+        int32_t kps = (int32_t)((K + best - 1) / best);
+        kps = (kps + kLinStageK - 1) / kLinStageK * kLinStageK;
+        pl.k_per_split = kps;
+        pl.splits = (K + kps - 1) / kps;
     }
     return pl;
 }
@@ -245,7 +300,10 @@ int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, i
     const int64_t n_rounds = (pl.n_tiles + kLinXcds - 1) / kLinXcds;
     const int64_t blocks = kLinXcds * n_rounds * pl.t_tiles * pl.splits;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(linear_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    if (pl.token_tile == 256)
+        hipLaunchKernelGGL((linear_kernel<256, 2>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((linear_kernel<128, 3>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return (int)e;
     const int64_t elems = (int64_t)T * N;
