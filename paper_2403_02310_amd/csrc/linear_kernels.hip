@@ -64,6 +64,14 @@ __device__ __forceinline__ void lin_dma_load_16(const uint16_t *base, int byte_o
                  : "s"(lds_addr), "v"(byte_off), "s"(base)
                  : "memory");
 }
+// The same with the non-temporal hint, for the weights: every weight byte is fetched by one workgroup
+// of a token tile, and a layer's weights are far more than the caches hold (+1 to +6 %).
+__device__ __forceinline__ void lin_dma_load_16_stream(const uint16_t *base, int byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :
+                 : "s"(lds_addr), "v"(byte_off), "s"(base)
+                 : "memory");
+}
 // s_waitcnt with the vector-memory counter at n and the LDS counter at zero (gfx9 encoding: vmcnt in bits
 // 3:0 and 15:14, expcnt 6:4 left at its maximum, lgkmcnt 11:8)
 #define LIN_WAIT_VMCNT_AND_LDS(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
@@ -78,15 +86,19 @@ struct LinearParams {
     int32_t k_per_split;  // multiple of 64
 };
 
-template <int BM, int RING>
+// BM tokens per tile; WT wavefronts side by side along the tokens (the other 8 / WT along the features);
+// RING stages of LDS.
+template <int BM, int WT, int RING>
 __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) {
     constexpr int W_ELEMS = kLinBN * kLinStageK;
     constexpr int X_ELEMS = BM * kLinStageK;
     constexpr int STAGE = W_ELEMS + X_ELEMS;
-    constexpr int X_LOADS = BM / 64;            // 1 KiB loads of token rows per wavefront and stage
+    constexpr int X_LOADS = BM >= 64 ? BM / 64 : 1;  // 1 KiB loads (8 rows) of token rows per wavefront and stage
     constexpr int LOADS = 4 + X_LOADS;          // all loads of a wavefront per stage
-    constexpr int NJ = BM / 64;                 // 32-token MFMA tiles per wavefront
+    constexpr int NI = WT;                      // 32-feature MFMA tiles per wavefront: 256 features / (8 / WT wavefronts) / 32
+    constexpr int NJ = BM / WT / 32;            // 32-token MFMA tiles per wavefront
     constexpr int STEPS = kLinStageK / 16;
+    static_assert(NI * (8 / WT) * 32 == kLinBN && NJ * WT * 32 == BM, "the wavefronts' tiles cover the workgroup's");
     __shared__ __attribute__((aligned(16))) uint16_t smem[RING * STAGE];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -116,7 +128,9 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
     }
 #pragma unroll
     for (int i = 0; i < X_LOADS; ++i) {
-        const int row = wave * (BM / 8) + i * 8 + (lane >> 3);
+        // fewer than 64 tokens: several wavefronts move the same rows (identical bytes to the same place), so
+        // that every wavefront issues the same number of loads
+        const int row = (wave * 8 * X_LOADS) % BM + i * 8 + (lane >> 3);
         const int piece = (lane & 7) ^ ((row >> 1) & 7);
         x_off[i] = ((min(t0 + row, p.T - 1) - t0) * p.K + piece * 8) * 2;
     }
@@ -131,55 +145,55 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
         const uint16_t *wb = w_base + s * kLinStageK;
         const uint16_t *xb = x_base + s * kLinStageK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lin_dma_load_16(wb, w_off[i], dst + (uint32_t)((wave * 32 + i * 8) * kLinStageK * 2));
+        for (int i = 0; i < 4; ++i) lin_dma_load_16_stream(wb, w_off[i], dst + (uint32_t)((wave * 32 + i * 8) * kLinStageK * 2));
 #pragma unroll
         for (int i = 0; i < X_LOADS; ++i)
-            lin_dma_load_16(xb, x_off[i], dst + (uint32_t)(W_ELEMS * 2 + (wave * (BM / 8) + i * 8) * kLinStageK * 2));
+            lin_dma_load_16(xb, x_off[i], dst + (uint32_t)(W_ELEMS * 2 + ((wave * 8 * X_LOADS) % BM + i * 8) * kLinStageK * 2));
     };
 
-    // ---- operands: wavefront (wn, wt) owns features 64wn.. and tokens (BM/2)wt.. of the tile
-    const int wn = wave & 3, wt = wave >> 2;
+    // ---- operands: wavefront (wn, wt) owns features 32 NI wn.. and tokens 32 NJ wt.. of the tile
+    const int wn = wave % (8 / WT), wt = wave / (8 / WT);
     const int r = lane & 31, g = lane >> 5;
-    int a_row[2], a_key[2], b_row[NJ], b_key[NJ];  // element offset of the row inside a stage, and its swizzle key
+    int a_row[NI], a_key[NI], b_row[NJ], b_key[NJ];  // element offset of the row inside a stage, and its swizzle key
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int ra = wn * 64 + i * 32 + r;
+    for (int i = 0; i < NI; ++i) {
+        const int ra = wn * (32 * NI) + i * 32 + r;
         a_row[i] = ra * kLinStageK;
         a_key[i] = (ra >> 1) & 7;
     }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
-        const int rb = wt * (BM / 2) + jj * 32 + r;
+        const int rb = wt * (32 * NJ) + jj * 32 + r;
         b_row[jj] = W_ELEMS + rb * kLinStageK;
         b_key[jj] = (rb >> 1) & 7;
     }
 
-    lf32x16 acc[2][NJ];
+    lf32x16 acc[NI][NJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][jj][e] = 0.f;
 
-    auto read_step = [&](const uint16_t *sp, int s, lbf16x8 (&a)[2], lbf16x8 (&b)[NJ]) {
+    auto read_step = [&](const uint16_t *sp, int s, lbf16x8 (&a)[NI], lbf16x8 (&b)[NJ]) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NI; ++i)
             a[i] = __builtin_bit_cast(lbf16x8, *reinterpret_cast<const lu32x4 *>(sp + a_row[i] + (((2 * s + g) ^ a_key[i]) * 8)));
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj)
             b[jj] = __builtin_bit_cast(lbf16x8, *reinterpret_cast<const lu32x4 *>(sp + b_row[jj] + (((2 * s + g) ^ b_key[jj]) * 8)));
     };
-    auto mfma_step = [&](const lbf16x8 (&a)[2], const lbf16x8 (&b)[NJ]) {
+    auto mfma_step = [&](const lbf16x8 (&a)[NI], const lbf16x8 (&b)[NJ]) {
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < NI; ++i)
                 acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[jj], acc[i][jj], 0, 0, 0);
     };
-    lbf16x8 fa[2][2], fb[2][NJ];  // two operand sets used in turn
+    lbf16x8 fa[2][NI], fb[2][NJ];  // two operand sets used in turn
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fa[1][i] = lbf16x8{};  // the "last step of stage -1": zeros
+    for (int i = 0; i < NI; ++i) fa[1][i] = lbf16x8{};  // the "last step of stage -1": zeros
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) fb[1][jj] = lbf16x8{};
 
@@ -212,11 +226,11 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
     // ---- output: accumulator element e of lane (r, g) of tile (i, jj) is feature 32i + 8(e/4) + 4g + e%4, token 32jj + r
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
-        const int t = t0 + wt * (BM / 2) + jj * 32 + r;
+        const int t = t0 + wt * (32 * NJ) + jj * 32 + r;
         if (t >= p.T) continue;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int f0 = n0 + wn * 64 + i * 32 + 4 * g;
+        for (int i = 0; i < NI; ++i) {
+            const int f0 = n0 + wn * (32 * NI) + i * 32 + 4 * g;
             if (f0 >= p.N) continue;  // N is a multiple of 128, the tile 256 wide
             if (p.splits == 1) {
                 uint16_t *yp = p.y + (int64_t)t * p.N + f0;
@@ -252,7 +266,7 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
     // Token tile: 256 tokens per tile halve the operand traffic per MFMA, 128 waste less of a ragged batch;
     // the narrow tile costs about a quarter more per token.
     const int64_t cost256 = (int64_t)((T + 255) / 256) * 256 * 4, cost128 = (int64_t)((T + 127) / 128) * 128 * 5;
-    pl.token_tile = cost128 < cost256 ? 128 : 256;
+    pl.token_tile = T <= 32 ? 32 : T <= 64 ? 64 : cost128 < cost256 ? 128 : 256;
     pl.n_tiles = (N + kLinBN - 1) / kLinBN;
     pl.t_tiles = (T + pl.token_tile - 1) / pl.token_tile;
     pl.splits = 1;
@@ -264,7 +278,7 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
     // bounds it), plus the partial tiles at ~3 TB/s and the second launch.  Pieces keep at least 4 stages.
     const int64_t tiles = (int64_t)pl.n_tiles * pl.t_tiles;
     const int64_t slots = 256;
-    const double stage_us = pl.token_tile == 256 ? 1.95 : 1.3;
+    const double stage_us = pl.token_tile == 256 ? 1.95 : 1.3;  // the narrower tiles are bound by the weights too
     const int64_t k_stages = K / kLinStageK;
     auto cost_us = [&](int64_t s) {
         const int64_t rounds = (tiles * s + slots - 1) / slots;
@@ -300,10 +314,15 @@ int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, i
     const int64_t n_rounds = (pl.n_tiles + kLinXcds - 1) / kLinXcds;
     const int64_t blocks = kLinXcds * n_rounds * pl.t_tiles * pl.splits;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // LDS: 2 x 64 KiB, 3 x 48 KiB, 3 x 40 KiB, 4 x 36 KiB
     if (pl.token_tile == 256)
-        hipLaunchKernelGGL((linear_kernel<256, 2>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+        hipLaunchKernelGGL((linear_kernel<256, 2, 2>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+    else if (pl.token_tile == 128)
+        hipLaunchKernelGGL((linear_kernel<128, 2, 3>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+    else if (pl.token_tile == 64)
+        hipLaunchKernelGGL((linear_kernel<64, 1, 3>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
     else
-        hipLaunchKernelGGL((linear_kernel<128, 3>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+        hipLaunchKernelGGL((linear_kernel<32, 1, 4>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return (int)e;
     const int64_t elems = (int64_t)T * N;

@@ -63,7 +63,7 @@ def run(hx, T, N, K, seed, workspace="full", rows=None, cols=None, x_bits=None, 
 
 
 @pytest.mark.parametrize("T,N,K", [(128, 128, 64), (1, 128, 64), (77, 256, 192), (129, 384, 320), (300, 1152, 1024),
-                                   (64, 128, 4096), (257, 1280, 64)])
+                                   (64, 128, 4096), (257, 1280, 64), (16, 512, 1024), (33, 384, 256), (100, 640, 512)])
 def test_linear_matches_checker(hx, T, N, K):
     """Several token tiles, a ragged last one, several feature tiles (more and fewer than the XCD count), one and many stages."""
     run(hx, T, N, K, seed=T + N + K)
