@@ -88,16 +88,19 @@ struct LinearParams {
 
 // BM tokens per tile; WT wavefronts side by side along the tokens (the other 8 / WT along the features);
 // RING stages of LDS.
-template <int BM, int WT, int RING>
+template <int BM, int WT, int RING, int KS = kLinStageK>
 __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) {
-    constexpr int W_ELEMS = kLinBN * kLinStageK;
-    constexpr int X_ELEMS = BM * kLinStageK;
+    constexpr int PIECES = KS / 8;              // 16-byte pieces of an LDS row
+    constexpr int DMA_ROWS = 64 / PIECES;       // rows one 1 KiB load covers
+    constexpr int W_ELEMS = kLinBN * KS;
+    constexpr int X_ELEMS = BM * KS;
     constexpr int STAGE = W_ELEMS + X_ELEMS;
-    constexpr int X_LOADS = BM >= 64 ? BM / 64 : 1;  // 1 KiB loads (8 rows) of token rows per wavefront and stage
-    constexpr int LOADS = 4 + X_LOADS;          // all loads of a wavefront per stage
+    constexpr int W_LOADS = 32 / DMA_ROWS;      // 1 KiB loads of weight rows per wavefront and stage
+    constexpr int X_LOADS = BM >= 8 * DMA_ROWS ? BM / (8 * DMA_ROWS) : 1;  // the same for token rows
+    constexpr int LOADS = W_LOADS + X_LOADS;    // all loads of a wavefront per stage
     constexpr int NI = WT;                      // 32-feature MFMA tiles per wavefront: 256 features / (8 / WT wavefronts) / 32
     constexpr int NJ = BM / WT / 32;            // 32-token MFMA tiles per wavefront
-    constexpr int STEPS = kLinStageK / 16;
+    constexpr int STEPS = KS / 16;
     static_assert(NI * (8 / WT) * 32 == kLinBN && NJ * WT * 32 == BM, "the wavefronts' tiles cover the workgroup's");
     __shared__ __attribute__((aligned(16))) uint16_t smem[RING * STAGE];
     const int lane = threadIdx.x & 63;
@@ -114,24 +117,25 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
     const int t0 = t_tile * BM;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);
-    const int n_stages = (k_end - k_begin) / kLinStageK;
+    const int n_stages = (k_end - k_begin) / KS;
+    auto row_key = [](int row) { return KS == 64 ? (row >> 1) & 7 : (row >> 2) & 3; };
 
     // ---- global -> LDS: wavefront w moves rows 32w .. 32w+31 of the weight tile (four loads of 8 rows) and
     // rows (BM/8)w .. of the token tile.  Lane l of a load fills physical piece l % 8 of row l / 8 and
     // therefore fetches the logical piece that lives there.  Rows past the matrix re-read its last row.
-    int w_off[4], x_off[X_LOADS];
+    int w_off[W_LOADS], x_off[X_LOADS];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = wave * 32 + i * 8 + (lane >> 3);
-        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+    for (int i = 0; i < W_LOADS; ++i) {
+        const int row = wave * 32 + i * DMA_ROWS + lane / PIECES;
+        const int piece = (lane % PIECES) ^ row_key(row);
         w_off[i] = ((min(n0 + row, p.N - 1) - n0) * p.K + piece * 8) * 2;
     }
 #pragma unroll
     for (int i = 0; i < X_LOADS; ++i) {
         // fewer than 64 tokens: several wavefronts move the same rows (identical bytes to the same place), so
         // that every wavefront issues the same number of loads
-        const int row = (wave * 8 * X_LOADS) % BM + i * 8 + (lane >> 3);
-        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = (wave * DMA_ROWS * X_LOADS) % BM + i * DMA_ROWS + lane / PIECES;
+        const int piece = (lane % PIECES) ^ row_key(row);
         x_off[i] = ((min(t0 + row, p.T - 1) - t0) * p.K + piece * 8) * 2;
     }
     const uint16_t *w_base = p.w + (int64_t)n0 * p.K + k_begin;
@@ -142,13 +146,13 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
         // number of loads, so one wait count serves the whole loop
         const int s = min(stage, n_stages - 1);
         const uint32_t dst = smem_addr + (uint32_t)(slot * STAGE * 2);
-        const uint16_t *wb = w_base + s * kLinStageK;
-        const uint16_t *xb = x_base + s * kLinStageK;
+        const uint16_t *wb = w_base + s * KS;
+        const uint16_t *xb = x_base + s * KS;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lin_dma_load_16_stream(wb, w_off[i], dst + (uint32_t)((wave * 32 + i * 8) * kLinStageK * 2));
+        for (int i = 0; i < W_LOADS; ++i) lin_dma_load_16_stream(wb, w_off[i], dst + (uint32_t)((wave * 32 + i * DMA_ROWS) * KS * 2));
 #pragma unroll
         for (int i = 0; i < X_LOADS; ++i)
-            lin_dma_load_16(xb, x_off[i], dst + (uint32_t)(W_ELEMS * 2 + ((wave * 8 * X_LOADS) % BM + i * 8) * kLinStageK * 2));
+            lin_dma_load_16(xb, x_off[i], dst + (uint32_t)(W_ELEMS * 2 + ((wave * DMA_ROWS * X_LOADS) % BM + i * DMA_ROWS) * KS * 2));
     };
 
     // ---- operands: wavefront (wn, wt) owns features 32 NI wn.. and tokens 32 NJ wt.. of the tile
@@ -158,14 +162,14 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int ra = wn * (32 * NI) + i * 32 + r;
-        a_row[i] = ra * kLinStageK;
-        a_key[i] = (ra >> 1) & 7;
+        a_row[i] = ra * KS;
+        a_key[i] = row_key(ra);
     }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = wt * (32 * NJ) + jj * 32 + r;
-        b_row[jj] = W_ELEMS + rb * kLinStageK;
-        b_key[jj] = (rb >> 1) & 7;
+        b_row[jj] = W_ELEMS + rb * KS;
+        b_key[jj] = row_key(rb);
     }
 
     lf32x16 acc[NI][NJ];
