@@ -1,9 +1,11 @@
 // gfx950 kernels of libsarathi: KV append, hybrid-batch attention over the paged cache,
 // and the split-KV merge.
 //
-// Attention kernel (16-column wave tile).  One wavefront owns one work item: 16 query
-// COLUMNS (col = row*G + head_in_group, all sharing one KV head) against a key range, walked
-// in tiles of 32 keys (two pages).  Both contractions run on v_mfma_f32_16x16x32_bf16 in the
+// Attention kernel (16-column wave tile).  A work item is 16 query COLUMNS (col = row*G +
+// head_in_group, all sharing one KV head) against a key range; a workgroup of four wavefronts owns
+// it, each wavefront walks a quarter of the keys in tiles of 32 (two pages), and the four results
+// are merged in LDS (a decode has four memory streams from its first cycle and ends four times
+// sooner than on one wavefront).  Both contractions run on v_mfma_f32_16x16x32_bf16 in the
 // TRANSPOSED form so that the score accumulators already are the operand of the second one:
 //
 //   S^T[key, col] = sum_c K[key, c] * Q[col, c]      A = K tile (16 keys x 32 ch), B = Q^T
@@ -16,7 +18,8 @@
 // scores of column n for keys 8g..8g+7 of the tile: exactly the B operand (P^T) of the second
 // contraction, and V^T for those eight keys is one 16-byte run of the channel-major V page.
 // So K, V and Q go from global memory straight into MFMA operands: no LDS, no transposes, no
-// barriers; the softmax is per-lane work plus two cross-lane steps (lanes n, n+16, n+32, n+48).
+// barriers in the key loop; the softmax is per-lane work plus two cross-lane steps (lanes n, n+16,
+// n+32, n+48).
 //
 // Chunk-tile path (prefill chunks).  A workgroup of four wavefronts owns 128 columns of one
 // sequence (32 per wave) and walks the key range in 32-key tiles staged once per workgroup in
@@ -28,9 +31,9 @@
 // XOR-swizzled in LDS and the two 16-byte halves of a V^T row are swapped on every other group
 // of eight channels, which makes both the staging writes and the operand reads bank-conflict free.
 //
-// Both paths share one launch: a block is either one chunk tile or four independent wave
-// tiles, so the memory-bound decodes fill the machine next to the MFMA-bound chunk tiles (the
-// paper's reason for hybrid batches, section 4.1).
+// Both paths share one launch: a block is either one chunk tile or one wave tile, so the
+// memory-bound decodes fill the machine next to the MFMA-bound chunk tiles (the paper's reason
+// for hybrid batches, section 4.1).
 //
 // The running maximum is only raised when a tile exceeds it by more than 2^8 (the softmax is
 // invariant to the reference point as long as sum and output use the same one), which removes
