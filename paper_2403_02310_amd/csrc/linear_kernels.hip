@@ -266,44 +266,47 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(const float *part, u
 }  // namespace
 
 LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) {
-    LinearPlan pl;
-    // Token tile: 256 tokens per tile halve the operand traffic per MFMA, 128 waste less of a ragged batch;
-    // the narrow tile costs about a quarter more per token.
-    const int64_t cost256 = (int64_t)((T + 255) / 256) * 256 * 4, cost128 = (int64_t)((T + 127) / 128) * 128 * 5;
-    pl.token_tile = T <= 32 ? 32 : T <= 64 ? 64 : cost128 < cost256 ? 128 : 256;
-    pl.n_tiles = (N + kLinBN - 1) / kLinBN;
-    pl.t_tiles = (T + pl.token_tile - 1) / pl.token_tile;
-    pl.splits = 1;
-    pl.k_per_split = K;
-    // Fewer workgroups than compute units, or a ragged last round of them: cutting k into pieces fills
-    // the chip, at the price of fp32 partial tiles that are written, read back and added by a second
-    // kernel.  Rough cost of a piece count s, in microseconds: rounds of workgroups x stages per piece x
-    // the time of a stage (measured: ~1.95 us for 256 tokens, ~1.3 us for 128, where fetching the weights
-    // bounds it), plus the partial tiles at ~3 TB/s and the second launch.  Pieces keep at least 4 stages.
-    const int64_t tiles = (int64_t)pl.n_tiles * pl.t_tiles;
-    const int64_t slots = 256;
-    const double stage_us = pl.token_tile == 256 ? 1.95 : 1.3;  // the narrower tiles are bound by the weights too
+    // Rough cost of a tiling, in microseconds: rounds of workgroups (one per compute unit) x stages per piece x
+    // the time of a stage (measured: ~1.95 us for a 256-token tile; ~1.3 us for the narrower ones, where
+    // fetching the weights bounds it), plus, when the k range is cut into s pieces so that a small grid
+    // fills the chip, the fp32 partial tiles (written, read back and added by a second kernel) at
+    // ~3 TB/s and that kernel's launch.  Pieces keep at least 4 stages (256 k) and must fit the workspace.
+    const int64_t n_tiles = (N + kLinBN - 1) / kLinBN;
     const int64_t k_stages = K / kLinStageK;
-    auto cost_us = [&](int64_t s) {
-        const int64_t rounds = (tiles * s + slots - 1) / slots;
-        const double main_us = (double)rounds * (double)((k_stages + s - 1) / s) * stage_us;
-        return s == 1 ? main_us : main_us + 8.0 * (double)s * T * N / 3.0e6 + 5.0;
-    };
-    int64_t best = 1;
-    double best_cost = cost_us(1);
     const int64_t per_split_bytes = (int64_t)T * N * 4;
-    for (int64_t s = 2; s <= 16 && s * 4 <= k_stages; ++s) {
-        if ((size_t)(s * per_split_bytes) > workspace_bytes) break;
-        const double c = cost_us(s);
-        if (c < 0.95 * best_cost) { best_cost = c; best = s; }
+    const int64_t slots = 256;
+    LinearPlan best_plan{};
+    double best_cost = -1.0;
+    auto consider = [&](int32_t token_tile) {
+        const int64_t t_tiles = (T + token_tile - 1) / token_tile;
+        const int64_t tiles = n_tiles * t_tiles;
+        const double stage_us = token_tile == 256 ? 1.95 : 1.3;
+        for (int64_t s = 1; s <= 16 && (s == 1 || s * 4 <= k_stages); ++s) {
+            if (s > 1 && (size_t)(s * per_split_bytes) > workspace_bytes) break;
+            const int64_t rounds = (tiles * s + slots - 1) / slots;
+            double c = (double)rounds * (double)((k_stages + s - 1) / s) * stage_us;
+            if (s > 1) c += 8.0 * (double)s * T * N / 3.0e6 + 5.0;
+            if (best_cost < 0.0 || c < 0.95 * best_cost) {
+                best_cost = c;
+                best_plan.token_tile = token_tile;
+                best_plan.n_tiles = (int32_t)n_tiles;
+                best_plan.t_tiles = (int32_t)t_tiles;
+                int32_t kps = (int32_t)((K + s - 1) / s);
+                kps = (kps + kLinStageK - 1) / kLinStageK * kLinStageK;
+                best_plan.k_per_split = s == 1 ? K : kps;
+                best_plan.splits = s == 1 ? 1 : (K + kps - 1) / kps;
+            }
+        }
+    };
+    // Token tile: the smallest that holds a small batch; from 65 tokens on, 256 tokens per tile halve the
+    // operand traffic per MFMA, 128 waste less of a ragged batch and give twice the workgroups.
+    if (T <= 32) consider(32);
+    else if (T <= 64) consider(64);
+    else {
+        consider(256);
+        consider(128);
     }
-    if (best > 1) {
-        int32_t kps = (int32_t)((K + best - 1) / best);
-        kps = (kps + kLinStageK - 1) / kLinStageK * kLinStageK;
-        pl.k_per_split = kps;
-        pl.splits = (K + kps - 1) / kps;
-    }
-    return pl;
+    return best_plan;
 }
 
 int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, int32_t T, int32_t N, int32_t K,
