@@ -15,6 +15,7 @@ def test_profile_and_pick():
     rows = tb.profile(timer, shape, [64, 512, 2048], [700] * 8, chunk_prefix=1500, seed=3)
     print(rows, flush=True)
     assert rows[0]["seconds"] < rows[2]["seconds"]                      # 56 vs 2040 chunk rows on a 1500-token prefix
-    pick = tb.compute_token_budget(rows, rows[1]["seconds"] * 1.05)
+    # a target that the two smaller budgets meet whatever the noise between them (both are launch-bound here)
+    pick = tb.compute_token_budget(rows, max(rows[0]["seconds"], rows[1]["seconds"]) * 1.05)
     assert pick in (512, 2048)
     assert tb.compute_token_budget(rows, min(r["seconds"] for r in rows) * 0.5) is None   # a target nothing meets
