@@ -109,7 +109,10 @@ def test_model_shapes_sampled(hx):
     """The layer shapes bench.py times (Mistral-7B feed-forward up/gate and down projections) at two token counts,
     on sampled rows and columns."""
     rng = np.random.default_rng(17)
-    for (T, N, K) in [(128, 28672, 4096), (2048, 4096, 14336), (640, 6144, 4096)]:
+    # ... and Falcon-180B's QKV (a feature count that is not a multiple of the 256-feature tile) and attention
+    # output projection (58 stages of 64 k) under TP4, LLaMA2-70B's QKV under TP4 at a decode-sized batch
+    for (T, N, K) in [(128, 28672, 4096), (2048, 4096, 14336), (640, 6144, 4096), (200, 3968, 14848), (2048, 14848, 3712),
+                      (48, 2560, 8192)]:
         rows = sorted(set([0, T - 1, 127 % T, 128 % T] + rng.integers(0, T, 12).tolist()))
         cols = sorted(set([0, N - 1, 127, 128, 1023, 1024] + rng.integers(0, N, 40).tolist()))
         run(hx, T, N, K, seed=21, rows=rows, cols=cols)
