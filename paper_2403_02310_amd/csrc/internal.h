@@ -165,8 +165,9 @@ int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32
 
 // ---- linear layer (linear_kernels.hip) ----
 struct LinearPlan {
+    int32_t feature_tile; // output features per workgroup tile: 256 or 128
     int32_t token_tile;   // tokens per workgroup tile: 256, 128, 64 or 32
-    int32_t n_tiles;      // 256-feature tiles
+    int32_t n_tiles;      // feature tiles
     int32_t t_tiles;      // token tiles
     int32_t splits;       // pieces of the k range (1 = none); pieces write fp32 partial tiles
     int32_t k_per_split;  // multiple of 64

@@ -87,21 +87,22 @@ struct LinearParams {
 };
 
 // BM tokens per tile; WT wavefronts side by side along the tokens (the other 8 / WT along the features);
-// RING stages of LDS.
-template <int BM, int WT, int RING, int KS = kLinStageK>
+// RING stages of LDS; BN features per tile (256, or 128 for matrices too small to fill the chip with wide tiles).
+template <int BM, int WT, int RING, int KS = kLinStageK, int BN = kLinBN>
 __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) {
     constexpr int PIECES = KS / 8;              // 16-byte pieces of an LDS row
     constexpr int DMA_ROWS = 64 / PIECES;       // rows one 1 KiB load covers
-    constexpr int W_ELEMS = kLinBN * KS;
+    constexpr int W_ELEMS = BN * KS;
     constexpr int X_ELEMS = BM * KS;
     constexpr int STAGE = W_ELEMS + X_ELEMS;
-    constexpr int W_LOADS = 32 / DMA_ROWS;      // 1 KiB loads of weight rows per wavefront and stage
+    constexpr int W_ROWS = BN / 8;              // weight rows a wavefront moves per stage
+    constexpr int W_LOADS = W_ROWS / DMA_ROWS;  // 1 KiB loads of weight rows per wavefront and stage
     constexpr int X_LOADS = BM >= 8 * DMA_ROWS ? BM / (8 * DMA_ROWS) : 1;  // the same for token rows
     constexpr int LOADS = W_LOADS + X_LOADS;    // all loads of a wavefront per stage
-    constexpr int NI = WT;                      // 32-feature MFMA tiles per wavefront: 256 features / (8 / WT wavefronts) / 32
+    constexpr int NI = BN * WT / 256;           // 32-feature MFMA tiles per wavefront: BN features / (8 / WT wavefronts) / 32
     constexpr int NJ = BM / WT / 32;            // 32-token MFMA tiles per wavefront
     constexpr int STEPS = KS / 16;
-    static_assert(NI * (8 / WT) * 32 == kLinBN && NJ * WT * 32 == BM, "the wavefronts' tiles cover the workgroup's");
+    static_assert(NI * (8 / WT) * 32 == BN && NJ * WT * 32 == BM, "the wavefronts' tiles cover the workgroup's");
     __shared__ __attribute__((aligned(16))) uint16_t smem[RING * STAGE];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
     const int split = j % p.splits;
     const int n_tile = xcd + kLinXcds * (j / p.splits);
     if (n_tile >= p.n_tiles) return;
-    const int n0 = n_tile * kLinBN;
+    const int n0 = n_tile * BN;
     const int t0 = t_tile * BM;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
     int w_off[W_LOADS], x_off[X_LOADS];
 #pragma unroll
     for (int i = 0; i < W_LOADS; ++i) {
-        const int row = wave * 32 + i * DMA_ROWS + lane / PIECES;
+        const int row = wave * W_ROWS + i * DMA_ROWS + lane / PIECES;
         const int piece = (lane % PIECES) ^ row_key(row);
         w_off[i] = ((min(n0 + row, p.N - 1) - n0) * p.K + piece * 8) * 2;
     }
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(kLinThreads, 1) void linear_kernel(LinearParams p) 
         const uint16_t *wb = w_base + s * KS;
         const uint16_t *xb = x_base + s * KS;
 #pragma unroll
-        for (int i = 0; i < W_LOADS; ++i) lin_dma_load_16_stream(wb, w_off[i], dst + (uint32_t)((wave * 32 + i * DMA_ROWS) * KS * 2));
+        for (int i = 0; i < W_LOADS; ++i) lin_dma_load_16_stream(wb, w_off[i], dst + (uint32_t)((wave * W_ROWS + i * DMA_ROWS) * KS * 2));
 #pragma unroll
         for (int i = 0; i < X_LOADS; ++i)
             lin_dma_load_16(xb, x_off[i], dst + (uint32_t)(W_ELEMS * 2 + ((wave * DMA_ROWS * X_LOADS) % BM + i * DMA_ROWS) * KS * 2));
@@ -271,18 +272,19 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
     // fetching the weights bounds it), plus, when the k range is cut into s pieces so that a small grid
     // fills the chip, the fp32 partial tiles (written, read back and added by a second kernel) at
     // ~3 TB/s and that kernel's launch.  Pieces keep at least 4 stages (256 k) and must fit the workspace.
-    const int64_t n_tiles = (N + kLinBN - 1) / kLinBN;
     const int64_t k_stages = K / kLinStageK;
     const int64_t per_split_bytes = (int64_t)T * N * 4;
     const int64_t slots = 256;
     LinearPlan best_plan{};
     double best_cost = -1.0;
-    auto consider = [&](int32_t token_tile) {
+    auto consider = [&](int32_t feature_tile, int32_t token_tile) {
+        const int64_t n_tiles = (N + feature_tile - 1) / feature_tile;
         const int64_t t_tiles = (T + token_tile - 1) / token_tile;
         const int64_t tiles = n_tiles * t_tiles;
         // a narrow tile next to others of its feature tile shares the weights and is bound by arithmetic (~15 % dearer
-        // per token than the 256-token tile); alone it is bound by fetching them
-        const double stage_us = token_tile == 256 ? 1.95 : (t_tiles >= 2 ? 1.12 : 1.3);
+        // per token than the 256-token tile); alone it is bound by fetching them.  The 128 x 128 tile is bound by
+        // the path global memory -> LDS: ~0.75 us for a quarter of the wide tile's arithmetic.
+        const double stage_us = feature_tile == 128 ? 0.75 : token_tile == 256 ? 1.95 : (t_tiles >= 2 ? 1.12 : 1.3);
         for (int64_t s = 1; s <= 16 && (s == 1 || s * 4 <= k_stages); ++s) {
             if (s > 1 && (size_t)(s * per_split_bytes) > workspace_bytes) break;
             const int64_t rounds = (tiles * s + slots - 1) / slots;
@@ -290,6 +292,7 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
             if (s > 1) c += 8.0 * (double)s * T * N / 3.0e6 + 5.0;
             if (best_cost < 0.0 || c < 0.95 * best_cost) {
                 best_cost = c;
+                best_plan.feature_tile = feature_tile;
                 best_plan.token_tile = token_tile;
                 best_plan.n_tiles = (int32_t)n_tiles;
                 best_plan.t_tiles = (int32_t)t_tiles;
@@ -301,12 +304,14 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
         }
     };
     // Token tile: the smallest that holds a small batch; from 65 tokens on, 256 tokens per tile halve the
-    // operand traffic per MFMA, 128 waste less of a ragged batch and give twice the workgroups.
-    if (T <= 32) consider(32);
-    else if (T <= 64) consider(64);
+    // operand traffic per MFMA, 128 waste less of a ragged batch and give twice the workgroups, and 128 x 128
+    // tiles give four times the workgroups to a matrix that is too small to fill the chip otherwise.
+    if (T <= 32) consider(256, 32);
+    else if (T <= 64) consider(256, 64);
     else {
-        consider(256);
-        consider(128);
+        consider(256, 256);
+        consider(256, 128);
+        consider(128, 128);
     }
     return best_plan;
 }
@@ -323,8 +328,10 @@ int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, i
     const int64_t n_rounds = (pl.n_tiles + kLinXcds - 1) / kLinXcds;
     const int64_t blocks = kLinXcds * n_rounds * pl.t_tiles * pl.splits;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // LDS: 2 x 64 KiB, 3 x 48 KiB, 3 x 40 KiB, 4 x 36 KiB
-    if (pl.token_tile == 256)
+    // LDS: 4 x 32 KiB, 2 x 64 KiB, 3 x 48 KiB, 3 x 40 KiB, 4 x 36 KiB
+    if (pl.feature_tile == 128)
+        hipLaunchKernelGGL((linear_kernel<128, 2, 4, kLinStageK, 128>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+    else if (pl.token_tile == 256)
         hipLaunchKernelGGL((linear_kernel<256, 2, 2>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
     else if (pl.token_tile == 128)
         hipLaunchKernelGGL((linear_kernel<128, 2, 3>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
