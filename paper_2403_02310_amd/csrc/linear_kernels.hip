@@ -8,16 +8,17 @@
 // a token is written in 8-byte pieces that a wavefront's accumulator tiles complete to 128
 // contiguous bytes.
 //
-// Workgroup = 8 wavefronts = a 256-feature x BM-token tile (BM = 256, or 128 for small batches),
-// wavefront = 64 features x BM/2 tokens of it (2 x 4 or 2 x 2 MFMA tiles).  What bounds a tile
+// Workgroup = 8 wavefronts = a 256-feature x BM-token tile (BM = 256; 128, 64 or 32 for small
+// batches; 128 x 128 for matrices too small to fill the chip with wide tiles), wavefront = 64 features
+// x BM/2 tokens of it (2 x 4 or 2 x 2 MFMA tiles; 32 x BM for the narrowest).  What bounds a tile
 // shape on this chip is the path global memory -> LDS (64 bytes per clock and compute unit): a
 // 128 x 128 tile needs 512 bytes of operands per MFMA, which is that path's whole bandwidth at
 // full MFMA rate (measured: 0.30 of the MFMA peak, 0.40 with half of the loads made redundant);
 // 256 x 256 needs half of it.  k advances in stages of 64, so that an LDS row is one full 128-byte
 // line of its matrix row; a stage (256 x 64 weights, BM x 64 tokens) goes from global memory
 // straight into LDS (global_load_lds_dwordx4: no staging registers) into a ring of two stages
-// (BM = 256: 128 KiB) or three (BM = 128: 144 KiB), one workgroup per compute unit, one barrier
-// per stage.  The eight 16-byte pieces of LDS row r are XOR-swizzled with (r >> 1) & 7 so that the
+// (BM = 256: 128 KiB), three (BM = 128: 144 KiB) or four, one workgroup per compute unit, one
+// barrier per stage.  The eight 16-byte pieces of LDS row r are XOR-swizzled with (r >> 1) & 7 so that the
 // 16 lanes of a b128 operand read, which walk 16 rows at one logical piece, hit distinct banks.
 // Inside a stage the loop is skewed by one k16 step: the operands of step s+1 are read while the
 // MFMAs of step s issue, and the last step's operands are carried over the barrier.
