@@ -132,9 +132,10 @@ def run_serving(args) -> int:
     seed = 31 if args.seed is None else args.seed
     qps = 8000.0   # attention alone is ~50x faster than a whole model's iteration: arrivals scaled to load it
     opts = {k: int(v) for k, v in (kv.split("=") for kv in args.opt)}
-    def run(reqs, policy, budget=512):
+    def run(reqs, policy, budget=512, linear_model=None):
         pages = int(1.3 * sum((r.total_rows + 15) // 16 for r in reqs))
-        loop = serving.ServingLoop(wl.MISTRAL_7B, reqs, serving.GpuBackend(seed=seed, keep_outputs=False, options=opts),
+        loop = serving.ServingLoop(wl.MISTRAL_7B, reqs, serving.GpuBackend(seed=seed, keep_outputs=False, options=opts,
+                                                                             linear_model=linear_model),
                                    num_pages=pages, token_budget=budget, chunk_size=budget, max_batch_size=128, policy=policy,
                                    seed=seed)
         return loop.run()
@@ -143,6 +144,11 @@ def run_serving(args) -> int:
     reqs = serving.synthetic_trace(seed, n_req, qps, max_prompt=8192, max_output=256)
     tokens = sum(r.total_rows for r in reqs)
     out = {policy: run(reqs, policy).summary() for policy in ("stall_free", "prefill_first")}
+    # the same with the four linear layers of one Mistral-7B transformer layer in every iteration: a longer trace-time
+    # scale (arrivals at a quarter of the rate), the operators that dominate a real iteration included
+    run(serving.synthetic_trace(seed + 1, 6, qps / 4, max_prompt=2048, max_output=16), "prefill_first", linear_model="mistral-7b")
+    reqs_l = serving.synthetic_trace(seed, n_req, qps / 4, max_prompt=8192, max_output=256)
+    out_l = {policy: run(reqs_l, policy, linear_model="mistral-7b").summary() for policy in ("stall_free", "prefill_first")}
     sf = out["stall_free"]
     print(json.dumps({
         "metric": "serving-loop proxy (KV append + attention only): generated tokens/s under stall-free batching",
@@ -152,7 +158,8 @@ def run_serving(args) -> int:
         "config": {"workload": "serve: %d requests, Poisson 8000/s, prompts lognormal(median 1730, p90 5696) <= 8192, outputs "
                                "lognormal(median 415, p90 834) <= 256, Mistral-7B attention shape, token budget 512" % n_req,
                    "attention_rows": tokens, "seed": seed},
-        "policies": out}))
+        "policies": out,
+        "policies_with_linear_layers": out_l}))
     return 0
 
 

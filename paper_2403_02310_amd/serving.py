@@ -133,11 +133,17 @@ class DryBackend:
 class GpuBackend:
     """Device memory (torch) + the two device entry points.  Fails loudly if the library is missing."""
 
-    def __init__(self, seed: int = 0, keep_outputs: bool = True, options: Optional[Dict[str, int]] = None):
+    def __init__(self, seed: int = 0, keep_outputs: bool = True, options: Optional[Dict[str, int]] = None,
+                 linear_model: Optional[str] = None):
+        """``linear_model`` (a key of ``linear_layers.MODELS``): every iteration also runs the four linear layers of
+        one transformer layer of that model over the iteration's tokens (random weights, outputs unused), so that the
+        timed iteration holds the operators that dominate a real one (section 3.1), not attention alone."""
         import torch
         from . import binding
         self.torch, self.binding = torch, binding
         self.seed, self.keep_outputs, self.options = seed, keep_outputs, dict(options or {})
+        self.linear_model = linear_model
+        self.linear = []
 
     def setup(self, loop: "ServingLoop") -> None:
         torch, s = self.torch, loop.shape
@@ -155,6 +161,17 @@ class GpuBackend:
             self.handle.set_option(k, v)
         self.sm_scale = 1.0 / float(np.sqrt(s.head_dim))
         self._ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        if self.linear_model:
+            from . import linear_layers as ll
+            scratch = 16
+            for _, n, k in ll.layer_shapes(ll.MODELS[self.linear_model]):
+                w = torch.randn(n, k, device="cuda", generator=g).to(torch.bfloat16)
+                x = torch.randn(loop.max_tokens, k, device="cuda", generator=g).to(torch.bfloat16)
+                y = torch.empty(loop.max_tokens, n, device="cuda", dtype=torch.bfloat16)
+                self.linear.append((x, w, y))
+                scratch = max([scratch] + [self.binding.linear_workspace_bytes(t, n, k)
+                                           for t in (16, 32, 64, 128, 256, 512, loop.max_tokens) if t <= loop.max_tokens])
+            self.linear_scratch = torch.empty(scratch, dtype=torch.uint8, device="cuda")
 
     def set_block_entries(self, slot: int, first_block: int, pages: Sequence[int]) -> None:
         t = self.torch.tensor(list(pages), dtype=self.torch.int32)
@@ -170,6 +187,9 @@ class GpuBackend:
         self._ev[0].record()
         self.handle.kv_append(k_new, v_new, self.k_cache, self.v_cache, bt, q_start, q_len, ctx_len)
         self.handle.hybrid_attention(q, self.k_cache, self.v_cache, bt, q_start, q_len, ctx_len, self.sm_scale, out)
+        n_tok = int(q.shape[0])
+        for x, w, y in self.linear:   # a smaller workspace than a token count would like only means fewer pieces
+            self.binding.linear(x[:n_tok], w, y[:n_tok], self.linear_scratch)
         self._ev[1].record()
         self._ev[1].synchronize()
         if self.out_all is not None:

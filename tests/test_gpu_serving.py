@@ -39,3 +39,27 @@ def test_requests_match_one_shot_attention(policy):
                                       [0], [0], [r.total_rows], [r.total_rows], scale)
         got = backend.out_all[a:b].to(torch.float64).cpu().numpy()
         compare(got, ref, "request %d (%d + %d rows) under %s" % (r.id, r.prompt_len, r.total_rows - r.prompt_len, policy))
+
+
+def test_iterations_with_linear_layers_leave_attention_unchanged():
+    """The backend can run the four linear layers of a transformer layer in every iteration (timing only): the
+    attention rows must still match, and the iterations must take longer than without them."""
+    shape = wl.AttnShape(8, 2, 128)
+    reqs = serving.synthetic_trace(23, 6, 50000.0, prompt_median=150, prompt_p90=420, output_median=8, output_p90=14,
+                                   max_prompt=600, max_output=16)
+    times = {}
+    for model in (None, "mistral-7b"):
+        backend = serving.GpuBackend(seed=5, linear_model=model)
+        loop = serving.ServingLoop(shape, reqs, backend, num_pages=400, token_budget=128, chunk_size=96, max_batch_size=16,
+                                   policy="stall_free", seed=2)
+        loop.run()
+        assert len(loop.done) == len(reqs)
+        times[model] = sum(it.duration_s for it in loop.iterations[2:])
+        scale = 1.0 / np.sqrt(shape.head_dim)
+        r = loop.done[0]
+        a, b = r.token_base, r.token_base + r.total_rows
+        ref = oracle.hybrid_attention(_bits(backend.q_all[a:b]), _bits(backend.k_all[a:b]), _bits(backend.v_all[a:b]),
+                                      [0], [0], [r.total_rows], [r.total_rows], scale)
+        compare(backend.out_all[a:b].to(torch.float64).cpu().numpy(), ref, "request %d, linear layers %s" % (r.id, model))
+    print("iteration seconds without / with linear layers:", times, flush=True)
+    assert times["mistral-7b"] > times[None]
