@@ -176,6 +176,14 @@ def run_token_budget(args) -> int:
     picks = {"%d us" % round(t * 1e6): tb.compute_token_budget(rows, t) for t in targets}
     quant = tb.tile_quantization_probe(timer, wl.MISTRAL_7B, prefix=2048, chunks=(223, 224, 225, 255, 256, 257, 288), seed=seed)
     t512 = [r for r in rows if r["token_budget"] == 512][0]["seconds"]
+    # the same with the four linear layers of one Mistral-7B transformer layer in the iteration (section 3.1: the
+    # operators that dominate it); tile quantisation now shows at the linear layers' 128/256-token tiles
+    timer_l = tb.gpu_timer({k: int(v) for k, v in (kv.split("=") for kv in args.opt)}, reps=max(5, min(args.steps, 30)),
+                           linear_model="mistral-7b")
+    rows_l = tb.profile(timer_l, wl.MISTRAL_7B, [64, 128, 256, 512, 1024, 2048, 4096], decode_ctx, chunk_prefix=2048, seed=seed)
+    targets_l = [300e-6, 500e-6, 1000e-6, 2000e-6]
+    picks_l = {"%d us" % round(t * 1e6): tb.compute_token_budget(rows_l, t) for t in targets_l}
+    quant_l = tb.tile_quantization_probe(timer_l, wl.MISTRAL_7B, prefix=2048, chunks=(255, 256, 257, 288, 384, 385, 512, 513), seed=seed)
     print(json.dumps({
         "metric": "token-budget profile (KV append + attention only): tokens/s of the budget-512 batch",
         "value": 512 / t512, "unit": "tokens/s", "n_gpus": 1, "steps": max(5, min(args.steps, 30)), "warmup": 3,
@@ -185,7 +193,11 @@ def run_token_budget(args) -> int:
                                "@prefix 2048", "seed": seed},
         "profile_us": {str(r["token_budget"]): r["seconds"] * 1e6 for r in rows},
         "largest_budget_within": picks,
-        "tile_quantization_us": {str(r["chunk"]): r["seconds"] * 1e6 for r in quant}}))
+        "tile_quantization_us": {str(r["chunk"]): r["seconds"] * 1e6 for r in quant},
+        "with_linear_layers": {"model": "mistral-7b (one transformer layer's four linear layers per iteration)",
+                               "profile_us": {str(r["token_budget"]): r["seconds"] * 1e6 for r in rows_l},
+                               "largest_budget_within": picks_l,
+                               "tile_quantization_us": {str(r["chunk"]): r["seconds"] * 1e6 for r in quant_l}}}))
     return 0
 
 

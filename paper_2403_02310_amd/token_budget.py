@@ -2,8 +2,9 @@
 
 The budget is found by a one-time profile: time batches with different numbers of tokens and take
 the largest count whose iteration stays within the latency target.  Here an "iteration" is KV append
-+ hybrid-batch attention only (there is no model around it), so the times are a PROXY for the
-paper's time-between-tokens target and the budgets only mean something relative to each other.
++ hybrid-batch attention, optionally plus the four linear layers of one transformer layer of a named
+model (``gpu_timer(linear_model=...)``); there is no whole model around it, so the times are a PROXY for
+the paper's time-between-tokens target and the budgets only mean something relative to each other.
 
 A profiled batch for budget tau = the given running decodes (one token each) plus one prefill chunk
 of tau - #decodes tokens on top of a cached prefix: the fullest batch stall-free batching builds
@@ -53,10 +54,28 @@ def compute_token_budget(rows: Sequence[Dict[str, float]], target_seconds: float
     return best
 
 
-def gpu_timer(options: Optional[Dict[str, int]] = None, reps: int = 20, warmup: int = 3) -> Callable[[HybridBatch], float]:
-    """Times append + attention of a batch on the GPU (median of ``reps``), values drawn on the device."""
+def gpu_timer(options: Optional[Dict[str, int]] = None, reps: int = 20, warmup: int = 3,
+              linear_model: Optional[str] = None) -> Callable[[HybridBatch], float]:
+    """Times append + attention of a batch on the GPU (median of ``reps``), values drawn on the device.
+    ``linear_model`` (a key of ``linear_layers.MODELS``): the four linear layers of one transformer layer of that
+    model run over the batch's tokens inside the timed region too."""
     import torch
     from . import binding
+    linear = []   # (weight, scratch bytes wanted) per layer, drawn once
+
+    def linear_operands(T: int):
+        from . import linear_layers as ll
+        if not linear:
+            g = torch.Generator(device="cuda").manual_seed(12345)
+            for _, n, k in ll.layer_shapes(ll.MODELS[linear_model]):
+                linear.append(torch.randn(n, k, device="cuda", generator=g).to(torch.bfloat16))
+        ops = []
+        for w in linear:
+            n, k = w.shape
+            ops.append((torch.ones(T, k, device="cuda", dtype=torch.bfloat16), w,
+                        torch.empty(T, n, device="cuda", dtype=torch.bfloat16),
+                        torch.empty(max(16, binding.linear_workspace_bytes(T, n, k)), dtype=torch.uint8, device="cuda")))
+        return ops
 
     def time_batch(b: HybridBatch) -> float:
         s = b.shape
@@ -72,11 +91,14 @@ def gpu_timer(options: Optional[Dict[str, int]] = None, reps: int = 20, warmup: 
         out = torch.empty_like(q)
         bt = torch.from_numpy(b.block_table).cuda()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        lin_ops = linear_operands(b.num_tokens) if linear_model else []
         times = []
         for i in range(warmup + reps):
             ev[0].record()
             h.kv_append(kn, vn, kc, vc, bt, b.q_start, b.q_len, b.ctx_len)
             h.hybrid_attention(q, kc, vc, bt, b.q_start, b.q_len, b.ctx_len, b.sm_scale, out)
+            for x, w, y, scratch in lin_ops:
+                binding.linear(x, w, y, scratch)
             ev[1].record()
             ev[1].synchronize()
             if i >= warmup:
