@@ -328,6 +328,7 @@ int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, i
     p.n_tiles = pl.n_tiles; p.t_tiles = pl.t_tiles; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
     const int64_t n_rounds = (pl.n_tiles + kLinXcds - 1) / kLinXcds;
     const int64_t blocks = kLinXcds * n_rounds * pl.t_tiles * pl.splits;
+    if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidValue;  // more workgroups than a grid holds
     hipStream_t st = static_cast<hipStream_t>(stream);
     // LDS: 4 x 32 KiB, 2 x 64 KiB, 3 x 48 KiB, 3 x 40 KiB, 4 x 36 KiB
     if (pl.feature_tile == 128)
