@@ -118,11 +118,14 @@ struct TileRegs {
     bf16x8 v[D / 16];     // A operands of the output MFMAs, per 16-channel tile
 };
 
+// Read-only int32 data fetched with scalar loads (the block table: wave-uniform indices).
+typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+
 template <int D>
 struct LaneGeom {
     const uint16_t *k_cache;
     const uint16_t *v_cache;
-    const int32_t *bt;     // this sequence's block-table row
+    const_i32_ptr bt;      // this sequence's block-table row (scalar loads)
     int64_t page_stride;   // elements per page (all KV heads)
     int64_t k_lane_off;    // element offset of this lane's K row start inside a page
     int64_t v_lane_off;    // element offset of this lane's V^T run inside a page
@@ -137,10 +140,14 @@ template <int D, bool STREAM>
 __device__ __forceinline__ void load_tile(const LaneGeom<D> &ge, int tile, TileRegs<D> &r) {
     // Pages at or beyond ceil(ctx_len/16) are never dereferenced: the index is clamped to the
     // sequence's last page and whatever is loaded for such keys is masked below.
-    int pik = min(tile * 2 + ge.k_pg_sel, ge.n_pages_seq - 1);
-    int piv = min(tile * 2 + ge.v_pg_sel, ge.n_pages_seq - 1);
-    int64_t pk = ge.bt[pik];
-    int64_t pv = ge.bt[piv];
+    // The tile's two table entries are wave-uniform: scalar loads, which the vector-memory counter does not
+    // see.  (As vector loads they were the youngest loads in flight when their values were needed, and
+    // loads return in order: waiting for them meant waiting for the previous tile's K/V too, so only one
+    // tile was ever in flight.)
+    const int32_t e0 = ge.bt[min(tile * 2, ge.n_pages_seq - 1)];
+    const int32_t e1 = ge.bt[min(tile * 2 + 1, ge.n_pages_seq - 1)];
+    int64_t pk = ge.k_pg_sel ? e1 : e0;
+    int64_t pv = ge.v_pg_sel ? e1 : e0;
     pk = pk < 0 ? 0 : (pk > ge.last_page_id ? ge.last_page_id : pk);
     pv = pv < 0 ? 0 : (pv > ge.last_page_id ? ge.last_page_id : pv);
     const uint16_t *kp = ge.k_cache + pk * ge.page_stride + ge.k_lane_off;
@@ -281,7 +288,7 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
     LaneGeom<D> ge;
     ge.k_cache = p.k_cache;
     ge.v_cache = p.v_cache;
-    ge.bt = p.block_table + (int64_t)seq * p.max_blocks;
+    ge.bt = (const_i32_ptr)(p.block_table + (int64_t)seq * p.max_blocks);
     ge.page_stride = (int64_t)p.num_kv_heads * kPageSize * D;
     ge.last_page_id = p.num_pages - 1;
     ge.n_pages_seq = (ctx + kPageSize - 1) / kPageSize;
@@ -433,7 +440,6 @@ __device__ __forceinline__ void dma_load_16(const uint16_t *base, int byte_off, 
 __device__ __forceinline__ uint32_t lds_address(const uint16_t *p) {
     return (uint32_t)(uintptr_t)(lds_ptr)(p);
 }
-typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
 // 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
