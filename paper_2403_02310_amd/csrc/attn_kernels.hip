@@ -135,23 +135,31 @@ struct LaneGeom {
     int32_t v_pg_sel;
 };
 
-// STREAM: the loads carry the non-temporal hint (K/V read once, far more than the caches hold).
-template <int D, bool STREAM>
-__device__ __forceinline__ void load_tile(const LaneGeom<D> &ge, int tile, TileRegs<D> &r) {
+// The two block-table entries of a 32-key tile.  They are wave-uniform and come by scalar loads, which the
+// vector-memory counter does not see.  (As vector loads they were the youngest loads in flight when their
+// values were needed, and loads return in order: waiting for them meant waiting for the previous tile's K/V
+// too, so only one tile was ever in flight.)
+struct TilePages {
+    int32_t e0, e1;
+};
+template <int D>
+__device__ __forceinline__ TilePages tile_pages(const LaneGeom<D> &ge, int tile) {
     // Pages at or beyond ceil(ctx_len/16) are never dereferenced: the index is clamped to the
-    // sequence's last page and whatever is loaded for such keys is masked below.
-    // The tile's two table entries are wave-uniform: scalar loads, which the vector-memory counter does not
-    // see.  (As vector loads they were the youngest loads in flight when their values were needed, and
-    // loads return in order: waiting for them meant waiting for the previous tile's K/V too, so only one
-    // tile was ever in flight.)
-    const int32_t e0 = ge.bt[min(tile * 2, ge.n_pages_seq - 1)];
-    const int32_t e1 = ge.bt[min(tile * 2 + 1, ge.n_pages_seq - 1)];
-    int64_t pk = ge.k_pg_sel ? e1 : e0;
-    int64_t pv = ge.v_pg_sel ? e1 : e0;
-    pk = pk < 0 ? 0 : (pk > ge.last_page_id ? ge.last_page_id : pk);
-    pv = pv < 0 ? 0 : (pv > ge.last_page_id ? ge.last_page_id : pv);
-    const uint16_t *kp = ge.k_cache + pk * ge.page_stride + ge.k_lane_off;
-    const uint16_t *vp = ge.v_cache + pv * ge.page_stride + ge.v_lane_off;
+    // sequence's last page and whatever is loaded for such keys is masked in compute_tile.
+    return TilePages{ge.bt[min(tile * 2, ge.n_pages_seq - 1)], ge.bt[min(tile * 2 + 1, ge.n_pages_seq - 1)]};
+}
+
+// Requests the K/V of `tile`, whose table entries arrive in `pages` (fetched a tile earlier), and fetches the
+// entries of the tile after it into `pages`.  The page bases are formed on the scalar unit; a lane only picks
+// one of the two.  STREAM: the loads carry the non-temporal hint (K/V read once, far more than the caches hold).
+template <int D, bool STREAM>
+__device__ __forceinline__ void load_tile(const LaneGeom<D> &ge, int tile, TileRegs<D> &r, TilePages &pages) {
+    const int64_t p0 = pages.e0 < 0 ? 0 : (pages.e0 > ge.last_page_id ? ge.last_page_id : (int64_t)pages.e0);
+    const int64_t p1 = pages.e1 < 0 ? 0 : (pages.e1 > ge.last_page_id ? ge.last_page_id : (int64_t)pages.e1);
+    pages = tile_pages(ge, tile + 1);
+    const int64_t o0 = p0 * ge.page_stride, o1 = p1 * ge.page_stride;
+    const uint16_t *kp = ge.k_cache + (ge.k_pg_sel ? o1 : o0) + ge.k_lane_off;
+    const uint16_t *vp = ge.v_cache + (ge.v_pg_sel ? o1 : o0) + ge.v_lane_off;
     if (STREAM) {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -310,12 +318,13 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
 
     // Two register sets, ping-pong: the loads of tile i+1 are in flight while tile i computes.
     TileRegs<D> ra, rb;
-    load_tile<D, STREAM>(ge, tile_begin, ra);
+    TilePages pages = tile_pages(ge, tile_begin);
+    load_tile<D, STREAM>(ge, tile_begin, ra, pages);
     int tile = tile_begin;
     for (; tile + 1 < tile_end; tile += 2) {
-        load_tile<D, STREAM>(ge, tile + 1, rb);
+        load_tile<D, STREAM>(ge, tile + 1, rb, pages);
         compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
-        if (tile + 2 < tile_end) load_tile<D, STREAM>(ge, tile + 2, ra);
+        if (tile + 2 < tile_end) load_tile<D, STREAM>(ge, tile + 2, ra, pages);
         compute_tile<D>(rb, qreg, st, tile + 1, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
     }
     if (tile < tile_end) compute_tile<D>(ra, qreg, st, tile, g, pos_eff, min_pos_eff, lo, max_lo, ctx, p.scale_log2);
