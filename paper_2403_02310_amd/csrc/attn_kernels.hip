@@ -433,18 +433,37 @@ __device__ __forceinline__ bf16x8 lds_bf16x8(const uint16_t *p) {
 
 typedef void __attribute__((address_space(3))) *lds_ptr;
 
-// One direct global -> LDS load of 16 bytes per lane (1 KiB per wavefront): lane l fetches
+// A direct global -> LDS load moves 16 bytes per lane (1 KiB per wavefront): lane l fetches
 // base + byte_off(l) and the wavefront's data lands at LDS byte address lds_addr + 16 l.
 // Written as inline assembly on purpose: the compiler's wait-count bookkeeping treats the
 // builtin form as a flat access that may return out of order with LDS reads, and from then on
 // turns every wait for an LDS operand into a full drain of the LDS queue (one pipeline bubble
 // per four MFMAs in the loop below).  The loads issued here are waited for by hand
 // (SARATHI_WAIT_VMCNT), the only vector-memory accesses of the chunk loop.
-__device__ __forceinline__ void dma_load_16(const uint16_t *base, int byte_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(byte_off), "s"(base)
-                 : "memory");
+// A whole page of one KV head (N loads of 1 KiB) behind ONE write of the LDS base register: the
+// instruction's immediate offset is added to the global address and to the LDS address alike, so
+// load j uses offset 1024 j and a lane offset that has 1024 j taken off (rel_off[j] = byte offset
+// inside the page minus 1024 j, which is never negative: load j fetches the page's j-th KiB).
+template <int N>
+__device__ __forceinline__ void dma_load_page(const uint16_t *base, const int (&rel_off)[N], uint32_t lds_addr) {
+    static_assert(N == 2 || N == 4, "pages of 2 KiB (d = 64) or 4 KiB (d = 128) per KV head");
+    if constexpr (N == 4) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %1, %5\n\t"
+                     "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+                     "global_load_lds_dwordx4 %4, %5 offset:3072"
+                     :
+                     : "s"(lds_addr), "v"(rel_off[0]), "v"(rel_off[1]), "v"(rel_off[2]), "v"(rel_off[3]), "s"(base)
+                     : "memory");
+    } else {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %1, %3\n\t"
+                     "global_load_lds_dwordx4 %2, %3 offset:1024"
+                     :
+                     : "s"(lds_addr), "v"(rel_off[0]), "v"(rel_off[1]), "s"(base)
+                     : "memory");
+    }
 }
 __device__ __forceinline__ uint32_t lds_address(const uint16_t *p) {
     return (uint32_t)(uintptr_t)(lds_ptr)(p);
@@ -702,7 +721,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     // K pages run three tiles ahead of the step, V pages two (V is consumed two steps later than K).
     const bool moves_v = wave >= 2;
     const int my_page = wave & 1;
-    int g_off[LOADS_PER_PAGE];  // this lane's byte offset inside the page of one KV head, per load
+    int g_off[LOADS_PER_PAGE];  // this lane's byte offset inside the page of one KV head, per load, minus 1024 j
 #pragma unroll
     for (int j = 0; j < LOADS_PER_PAGE; ++j) {
         const int q = j * 64 + lane;
@@ -710,7 +729,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         const int k_elem = k_slot * D + ((q % CPR) ^ k_swizzle<D>(k_slot)) * 8;
         const int v_d = q >> 1;
         const int v_elem = (v_d * 2 + ((q & 1) ^ ((v_d >> 3) & 1))) * 8;
-        g_off[j] = (moves_v ? v_elem : k_elem) * 2;
+        g_off[j] = (moves_v ? v_elem : k_elem) * 2 - j * 1024;  // relative to the load's own KiB (see dma_load_page)
     }
     const const_i32_ptr bt = (const_i32_ptr)(p.block_table + (int64_t)seq * p.max_blocks);  // read-only: scalar loads
     const int n_pages_seq = (ctx + kPageSize - 1) / kPageSize;
@@ -735,9 +754,7 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     auto issue_page = [&](int tile, int64_t pg) {
         const uint16_t *src = cache_head + pg * page_stride;
         const uint32_t dst = smem_addr + (uint32_t)(my_lds_base + ((tile - tile_begin) & (kRing - 1)) * TE) * 2;
-#pragma unroll
-        for (int j = 0; j < LOADS_PER_PAGE; ++j)
-            dma_load_16(src, g_off[j], dst + j * 1024);
+        dma_load_page<LOADS_PER_PAGE>(src, g_off, dst);
     };
     auto issue_tile = [&](int tile) { issue_page(tile, page_of(tile)); };
     const int my_ahead = moves_v ? 2 : 3;  // tiles this wave's loads run ahead of the step
@@ -789,7 +806,12 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     // Every step but a unit's last fetches this wave's page of tile t + my_ahead; beyond the
     // unit's end that is a clamped, unused page landing in a free ring slot, which keeps the loop
     // body and the load counter the same for all steps.
-    auto step = [&](int tile, auto has_prev, auto has_next, auto mask_next, auto with_dma, auto phase, auto pp) {
+    // pg_this: table entry of the page this step fetches; fetch_next: the step itself fetches the
+    // entry of the step after it (single steps), or the caller brings entries in batches (the unrolled
+    // group: while a scalar load is in flight every wait for an LDS read must wait for all of them,
+    // so one batch per four steps costs a quarter of what one load per step did).
+    auto step = [&](int tile, auto has_prev, auto has_next, auto mask_next, auto with_dma, auto phase, auto pp,
+                    int32_t pg_this, auto fetch_next) {
         // Tile t+1 must have landed (only this wave's loads of one later tile may still be in
         // flight), and every wave must be done with the slots about to be overwritten (K of
         // tile t-1, V of tile t-2).
@@ -798,8 +820,8 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         asm volatile("" ::: "memory");
         const int rel = tile - tile_begin;
         if (decltype(with_dma)::value) {
-            issue_page(tile + my_ahead, page_clamp(pg_next));
-            pg_next = page_raw(tile + my_ahead + 1);  // looked at in the next step only
+            issue_page(tile + my_ahead, page_clamp(pg_this));
+            if (decltype(fetch_next)::value) pg_next = page_raw(tile + my_ahead + 1);  // looked at in the next step only
         }
         // Raise the softmax reference of the columns whose due tile exceeds it by more than the slack
         // (rare).  Three things carry the old reference: the output accumulators (tiles up to t-2), the
@@ -834,31 +856,40 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
     using P2 = std::integral_constant<int, 2>;
     using P3 = std::integral_constant<int, 3>;
     if (n_tiles == 1) {
-        step(tile_begin, F{}, F{}, F{}, F{}, DYN{}, P0{});
+        step(tile_begin, F{}, F{}, F{}, F{}, DYN{}, P0{}, pg_next, F{});
     } else {
         // first tile: nothing to accumulate yet
-        if (tile_begin + 1 >= mask_from || tile_begin + 1 < mask_until) step(tile_begin, F{}, T{}, T{}, T{}, DYN{}, P0{});
-        else step(tile_begin, F{}, T{}, F{}, T{}, DYN{}, P0{});
+        if (tile_begin + 1 >= mask_from || tile_begin + 1 < mask_until) step(tile_begin, F{}, T{}, T{}, T{}, DYN{}, P0{}, pg_next, T{});
+        else step(tile_begin, F{}, T{}, F{}, T{}, DYN{}, P0{}, pg_next, T{});
         // steady state, unmasked tiles: groups of four steps with the ring slots and the register
         // sets compiled in (the group starts at tile index 1 modulo 4 and leaves the state in set 0),
         // then single steps up to the causal diagonal
         int tile = tile_begin + 1;
         // tiles in front of a sliding window's start (none without a window), then single steps up to the
         // tile index the unrolled group expects
-        for (; tile + 1 < tile_end && tile + 1 < mask_until; ++tile) step(tile, T{}, T{}, T{}, T{}, DYN{}, P0{});
+        for (; tile + 1 < tile_end && tile + 1 < mask_until; ++tile) step(tile, T{}, T{}, T{}, T{}, DYN{}, P0{}, pg_next, T{});
         for (; tile + 1 < tile_end && tile + 1 < mask_from && ((tile - tile_begin) & 3) != 1; ++tile)
-            step(tile, T{}, T{}, F{}, T{}, DYN{}, P0{});
-        for (; tile + 4 < tile_end && tile + 4 < mask_from; tile += 4) {
-            step(tile, T{}, T{}, F{}, T{}, P1{}, P0{});
-            step(tile + 1, T{}, T{}, F{}, T{}, P2{}, P1{});
-            step(tile + 2, T{}, T{}, F{}, T{}, P3{}, P0{});
-            step(tile + 3, T{}, T{}, F{}, T{}, P0{}, P1{});
+            step(tile, T{}, T{}, F{}, T{}, DYN{}, P0{}, pg_next, T{});
+        if (tile + 4 < tile_end && tile + 4 < mask_from) {
+            // table entries of the pages the group's steps fetch; the next group's come in one batch
+            int32_t e0 = pg_next, e1 = page_raw(tile + my_ahead + 1), e2 = page_raw(tile + my_ahead + 2),
+                    e3 = page_raw(tile + my_ahead + 3);
+            for (; tile + 4 < tile_end && tile + 4 < mask_from; tile += 4) {
+                const int32_t n0 = page_raw(tile + my_ahead + 4), n1 = page_raw(tile + my_ahead + 5),
+                              n2 = page_raw(tile + my_ahead + 6), n3 = page_raw(tile + my_ahead + 7);
+                step(tile, T{}, T{}, F{}, T{}, P1{}, P0{}, e0, F{});
+                step(tile + 1, T{}, T{}, F{}, T{}, P2{}, P1{}, e1, F{});
+                step(tile + 2, T{}, T{}, F{}, T{}, P3{}, P0{}, e2, F{});
+                step(tile + 3, T{}, T{}, F{}, T{}, P0{}, P1{}, e3, F{});
+                e0 = n0, e1 = n1, e2 = n2, e3 = n3;
+            }
+            pg_next = e0;
         }
-        for (; tile + 1 < tile_end && tile + 1 < mask_from; ++tile) step(tile, T{}, T{}, F{}, T{}, DYN{}, P0{});
+        for (; tile + 1 < tile_end && tile + 1 < mask_from; ++tile) step(tile, T{}, T{}, F{}, T{}, DYN{}, P0{}, pg_next, T{});
         // the tiles on the causal diagonal
-        for (; tile + 1 < tile_end; ++tile) step(tile, T{}, T{}, T{}, T{}, DYN{}, P0{});
+        for (; tile + 1 < tile_end; ++tile) step(tile, T{}, T{}, T{}, T{}, DYN{}, P0{}, pg_next, T{});
         // last tile: no further scores to form, nothing more to fetch (and no load left in flight after it)
-        step(tile_end - 1, T{}, F{}, F{}, F{}, DYN{}, P0{});
+        step(tile_end - 1, T{}, F{}, F{}, F{}, DYN{}, P0{}, pg_next, F{});
     }
     // Epilogue: the output MFMAs of the last tile.  Only here can a tile hold slots at or beyond
     // ctx_len (a unit never extends past the sequence), whose V bits must be zeroed: stale cache
