@@ -206,7 +206,7 @@ def run_linear(args) -> int:
     models of Table 1, one GPU's share under the paper's tensor-parallel degree."""
     from paper_2403_02310_amd import linear_layers as ll
     tokens = [16, 64, 128, 256, 384, 512, 768, 1024, 1536, 2048]
-    timer = ll.gpu_timer(reps=max(5, min(args.steps, 20)))
+    timer = ll.gpu_timer(reps=max(5, min(args.steps, 20)), zeros=args.values == "zeros")
     out = {}
     for key, m in ll.MODELS.items():
         shapes = ll.layer_shapes(m)
@@ -226,7 +226,7 @@ def run_linear(args) -> int:
         "metric": "linear layers of one transformer layer, tokens/s at 2048 tokens (LLaMA2-70B, one GPU of TP4)",
         "value": 2048 / t2048, "unit": "tokens/s", "n_gpus": 1, "steps": max(5, min(args.steps, 20)), "warmup": 3,
         "ms_per_step": t2048 * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if args.values == "normal" else "synthetic, ALL-ZERO values (clock diagnostic, not a reported figure)",
         "config": {"workload": "linear: QKV, attention-output, feed-forward up and down projections of the four models of "
                                "Table 1 at one GPU's tensor-parallel share, 16 ... 2048 tokens, N(0,1) values"},
         "roofline": {"bound": "mfma", "kernel": "linear_kernel", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -262,10 +262,16 @@ def main() -> int:
                          "(token-budget profile), linear (linear layers against the number of tokens)")
     ap.add_argument("--seed", type=int, default=None, help="seed of the workload recipe (default: the recipe's own)")
     ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
+    ap.add_argument("--values", choices=["normal", "zeros"], default="normal",
+                    help="normal: the workloads' N(0,1) values (every reported figure); zeros: all-zero Q/K/V or x/w, a "
+                         "diagnostic that shows how far the chip's clock, which falls with the matrix pipes' switching "
+                         "power, moves the MFMA-bound kernels (no parity check, no CPU baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--opt", action="append", default=[], help="library tuning knob name=value (repeatable)")
     args = ap.parse_args()
+    if args.values == "zeros":
+        args.no_cpu_baseline = True  # the checker's inputs are the workload's own values
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
                          "run with --gpus 1\n")
@@ -278,6 +284,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     from paper_2403_02310_amd import binding, harness
 
+    if args.values == "zeros" and args.workload in ("c5_sweep", "serve", "budget"):
+        sys.stderr.write("bench.py: --values zeros applies to the single-batch workloads and to --workload linear\n")
+        return 2
     if args.workload == "c5_sweep":
         return run_sweep(args, binding, harness, torch)
     if args.workload == "serve":
@@ -310,6 +319,9 @@ def main() -> int:
     k_new, v_new = harness.bits_to_device(k_new_bits), harness.bits_to_device(v_new_bits)
     qs = [harness.bits_to_device(batch.q_bits(c)) for c in range(copies)]
     outs = [torch.empty_like(qs[0]) for _ in range(copies)]
+    if args.values == "zeros":
+        for t in [k_new, v_new] + qs + [x for kv in pools for x in kv]:
+            t.zero_()
     del fill_handle
     torch.cuda.synchronize()
 
@@ -419,7 +431,7 @@ def main() -> int:
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if args.values == "normal" else "synthetic, ALL-ZERO values (clock diagnostic, not a reported figure)",
         "config": {"workload": args.workload + ": " + desc, "num_tokens": T, "num_seqs": S,
                    "sum_ctx_len": int(batch.ctx_len.astype(np.int64).sum()), "seed": batch.seed,
                    "kv_copies_rotated": copies, "plan": {"units": info.num_items, "chunk_tile_units": info.num_tile_items,

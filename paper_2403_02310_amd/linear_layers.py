@@ -71,9 +71,10 @@ def knee(rows: Sequence[dict]) -> float:
     return rows[0]["seconds"] / slope if slope > 0 else float("inf")
 
 
-def gpu_timer(reps: int = 20, warmup: int = 3, min_weight_bytes: int = 640 << 20):
+def gpu_timer(reps: int = 20, warmup: int = 3, min_weight_bytes: int = 640 << 20, zeros: bool = False):
     """Times sarathi_linear with HIP events; enough weight copies are rotated that a repetition never finds its
-    weights in the last-level cache (a model's layers are each read once per iteration)."""
+    weights in the last-level cache (a model's layers are each read once per iteration).  ``zeros``: all-zero
+    operands instead of N(0,1) values (a diagnostic: the chip's clock depends on the data the matrix pipes see)."""
     import torch
     from . import binding
 
@@ -82,6 +83,9 @@ def gpu_timer(reps: int = 20, warmup: int = 3, min_weight_bytes: int = 640 << 20
         g = torch.Generator(device="cuda").manual_seed(N * 31 + K)
         ws = [torch.randn(N, K, device="cuda", generator=g).to(torch.bfloat16) for _ in range(copies)]
         x = torch.randn(T, K, device="cuda", generator=g).to(torch.bfloat16)
+        if zeros:
+            for t in ws + [x]:
+                t.zero_()
         y = torch.empty(T, N, device="cuda", dtype=torch.bfloat16)
         nbytes = binding.linear_workspace_bytes(T, N, K)
         scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
