@@ -385,8 +385,13 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    # the attention kernel's duration is measured live by HIP events around every TIME_EVERY-th launch of the
+    # timed steps (an event record between two kernels holds the second back for ~6 us, so bracketing every
+    # launch would slow the very steps that are being timed by ~4 %)
+    TIME_EVERY = 8 if args.steps >= 64 else 1
     if not args.no_kernel_timing:
         handle.set_option("time_kernels", 1)
+        handle.set_option("time_every", TIME_EVERY)
         handle.kernel_times()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -401,6 +406,7 @@ def main() -> int:
     kt_all = None
     if not args.no_kernel_timing:
         handle.set_option("time_kernels", 2)
+        handle.set_option("time_every", 1)
         for i in range(min(args.steps, 50)):
             step(i)
         torch.cuda.synchronize()
@@ -453,8 +459,8 @@ def main() -> int:
             "merge": (kt_all.merge_ms * 1e3 / kt_all.merge_launches) if kt_all.merge_launches else 0.0,
             "kv_append": (kt_all.append_ms * 1e3 / kt_all.append_launches) if kt_all.append_launches else 0.0,
             "launches": int(kt.attention_launches),
-            "note": "attention: HIP events over the timed steps; merge (the part on the caller's stream) and "
-                    "kv_append: a separate pass of up to 50 steps"}
+            "note": "attention: HIP events around every %d-th launch of the timed steps; merge (the part on the caller's "
+                    "stream) and kv_append: a separate pass of up to 50 steps" % TIME_EVERY}
         mfma_bound = args.workload.endswith("_chunk") or args.workload.endswith("_chunks")
         # the launch the events bracket: one kernel holding both kinds of block when the batch has both
         has_chunk, has_wave = info.num_tile_items > 0, info.num_items > info.num_tile_items

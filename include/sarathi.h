@@ -108,7 +108,8 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * "window" (sliding-window attention as in the paper's Table 1 for Mistral-7B: with window W > 0 the
  * query at position p reads keys p-W+1 .. p only; 0 = every key up to p; pages in front of every
  * window of a sequence are never dereferenced),
- * "time_kernels" (0/1/2, see sarathi_get_kernel_times).
+ * "time_kernels" (0/1/2, see sarathi_get_kernel_times), "time_every" (n >= 1: only every n-th launch of a
+ * kind is bracketed, so that a timed run carries few events; default 1).
  * Unknown names return SARATHI_EINVAL. */
 sarathi_status sarathi_set_option(sarathi_handle *handle, const char *name, int64_t value);
 

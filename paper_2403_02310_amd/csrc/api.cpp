@@ -15,7 +15,8 @@
 using namespace sarathi;
 
 namespace {
-constexpr int kStagingSlots = 8;
+constexpr int kStagingSlots = 16;
+constexpr int kStagingHalf = kStagingSlots / 2;
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 }  // namespace
 
@@ -25,12 +26,18 @@ struct sarathi_handle {
     WorkspaceLayout ws;
     std::string err;
     Plan plan;
-    // Ring of pinned host buffers for the per-call metadata.  A slot is reused only after the
-    // copy that read it has completed (its event), so calls may be enqueued back to back
-    // without the host ever waiting in the steady state.
+    // Ring of pinned host buffers for the per-call metadata, in two halves.  An event is recorded behind the
+    // upload (a kernel that reads the pinned buffer) out of a half's LAST slot only, and waited for before the half's first slot is written again,
+    // half a ring of calls later: calls may be enqueued back to back without the host ever waiting in the
+    // steady state, and the stream carries one event per kStagingHalf calls instead of one per call (an
+    // event record between two kernels keeps the second from starting for ~6 us: kernel trace of the
+    // hybrid batch).  All copies out of a half go through one stream, so that its event covers them.
     void *staging[kStagingSlots] = {};
-    hipEvent_t staged[kStagingSlots] = {};
-    bool in_flight[kStagingSlots] = {};
+    void *staging_dev[kStagingSlots] = {};  // the same buffers as the device addresses them
+    hipEvent_t half_done[2] = {};
+    bool half_pending[2] = {};
+    hipStream_t half_stream[2] = {};
+    bool staging_used = false;
     size_t staging_bytes = 0;
     int next_slot = 0;
     bool staging_ready = false;
@@ -51,6 +58,8 @@ struct sarathi_handle {
     hipEvent_t fork_event = nullptr, join_event = nullptr;
     // Optional per-kernel timing: event pairs recorded around each launch.
     int time_kernels = 0;  // 0 off, 1 attention launches only, 2 also the append and merge kernels
+    int64_t time_every = 1;  // bracket every n-th launch of a kind only
+    uint64_t timing_seen[3] = {0, 0, 0};
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, merge
     size_t timing_used[3] = {0, 0, 0};
 };
@@ -72,22 +81,46 @@ sarathi_status ensure_staging(sarathi_handle *h) {
     for (int i = 0; i < kStagingSlots; ++i) {
         hipError_t e = hipHostMalloc(&h->staging[i], h->staging_bytes, hipHostMallocDefault);
         if (e != hipSuccess) return hip_fail(h, "hipHostMalloc(staging)", e);
-        e = hipEventCreateWithFlags(&h->staged[i], hipEventDisableTiming);
+        e = hipHostGetDevicePointer(&h->staging_dev[i], h->staging[i], 0);
+        if (e != hipSuccess) return hip_fail(h, "hipHostGetDevicePointer(staging)", e);
+    }
+    for (int i = 0; i < 2; ++i) {
+        hipError_t e = hipEventCreateWithFlags(&h->half_done[i], hipEventDisableTiming);
         if (e != hipSuccess) return hip_fail(h, "hipEventCreate", e);
     }
     h->staging_ready = true;
     return SARATHI_OK;
 }
 
-sarathi_status acquire_slot(sarathi_handle *h, int *slot) {
+sarathi_status acquire_slot(sarathi_handle *h, hipStream_t stream, int *slot) {
     const int s = h->next_slot;
-    h->next_slot = (s + 1) % kStagingSlots;
-    if (h->in_flight[s]) {
-        hipError_t e = hipEventSynchronize(h->staged[s]);
-        if (e != hipSuccess) return hip_fail(h, "hipEventSynchronize(staging slot)", e);
-        h->in_flight[s] = false;
+    const int half = s / kStagingHalf;
+    if (s % kStagingHalf == 0) {
+        if (h->half_pending[half]) {  // recorded half a ring of calls ago
+            hipError_t e = hipEventSynchronize(h->half_done[half]);
+            if (e != hipSuccess) return hip_fail(h, "hipEventSynchronize(staging half)", e);
+            h->half_pending[half] = false;
+        }
+        h->half_stream[half] = stream;
+    } else if (stream != h->half_stream[half]) {
+        // another stream inside a half: the half's event would not cover the copies already enqueued
+        hipError_t e = hipStreamSynchronize(h->half_stream[half]);
+        if (e != hipSuccess) return hip_fail(h, "hipStreamSynchronize(staging half)", e);
+        h->half_stream[half] = stream;
     }
+    h->next_slot = (s + 1) % kStagingSlots;
+    h->staging_used = true;
     *slot = s;
+    return SARATHI_OK;
+}
+
+// After the copy out of `slot` has been enqueued on `stream`.
+sarathi_status release_slot(sarathi_handle *h, int slot, hipStream_t stream) {
+    if (slot % kStagingHalf != kStagingHalf - 1) return SARATHI_OK;
+    const int half = slot / kStagingHalf;
+    hipError_t e = hipEventRecord(h->half_done[half], stream);
+    if (e != hipSuccess) return hip_fail(h, "hipEventRecord(staging half)", e);
+    h->half_pending[half] = true;
     return SARATHI_OK;
 }
 
@@ -96,6 +129,7 @@ constexpr size_t kMaxTimedLaunches = 8192;
 // Records the start event of a timed launch; returns the pair index or -1 when timing is off/full.
 int timing_begin(sarathi_handle *h, int kind, hipStream_t s) {
     if (h->time_kernels < (kind == 1 ? 1 : 2) || h->timing_used[kind] >= kMaxTimedLaunches) return -1;
+    if (h->timing_seen[kind]++ % (uint64_t)h->time_every != 0) return -1;
     auto &pool = h->timing_pool[kind];
     if (h->timing_used[kind] == pool.size()) {
         hipEvent_t a, b;
@@ -165,11 +199,12 @@ extern "C" sarathi_status sarathi_create(const sarathi_config *config, sarathi_h
 extern "C" sarathi_status sarathi_destroy(sarathi_handle *h) {
     if (!h) return SARATHI_EINVAL;
     if (h->staging_ready || h->staging[0]) {
-        for (int i = 0; i < kStagingSlots; ++i) {
-            if (h->in_flight[i]) (void)hipEventSynchronize(h->staged[i]);
-            if (h->staged[i]) (void)hipEventDestroy(h->staged[i]);
+        // copies out of the pinned buffers may still be queued (on streams this handle does not own)
+        if (h->staging_used) (void)hipDeviceSynchronize();
+        for (int i = 0; i < 2; ++i)
+            if (h->half_done[i]) (void)hipEventDestroy(h->half_done[i]);
+        for (int i = 0; i < kStagingSlots; ++i)
             if (h->staging[i]) (void)hipHostFree(h->staging[i]);
-        }
     }
     for (auto &pool : h->timing_pool)
         for (auto &pr : pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
@@ -237,6 +272,12 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
     if (std::strcmp(name, "time_kernels") == 0) {
         if (value < 0 || value > 2) return SARATHI_EINVAL;
         h->time_kernels = (int)value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "time_every") == 0) {
+        if (value < 1 || value > (1 << 20)) return fail(h, SARATHI_EINVAL, "time_every must be >= 1");
+        h->time_every = value;
+        for (auto &n : h->timing_seen) n = 0;
         return SARATHI_OK;
     }
     return fail(h, SARATHI_EINVAL, std::string("unknown option: ") + name);
@@ -311,9 +352,10 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     if (num_seqs == 0) return SARATHI_OK;
     if (!k_new || !v_new || !k_cache || !v_cache || !block_table) return fail(h, SARATHI_EINVAL, "null tensor pointer");
     if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return fail(h, SARATHI_EWORKSPACE, "workspace is not 256-byte aligned");
     if ((st = ensure_staging(h)) != SARATHI_OK) return st;
     int slot;
-    if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
+    if ((st = acquire_slot(h, static_cast<hipStream_t>(stream), &slot)) != SARATHI_OK) return st;
 
     // Metadata: one record per cache page that this iteration writes into.
     AppendUnit *units = static_cast<AppendUnit *>(h->staging[slot]);
@@ -350,11 +392,9 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
 
     char *dev = static_cast<char *>(workspace) + h->ws.meta;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(dev, units, used, hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "hipMemcpyAsync(metadata)", e); }
-    e = hipEventRecord(h->staged[slot], s);
-    if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
-    h->in_flight[slot] = true;
+    hipError_t e = (hipError_t)launch_upload(dev, h->staging_dev[slot], used, stream);
+    if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "launch upload(metadata)", e); }
+    if ((st = release_slot(h, slot, s)) != SARATHI_OK) return st;
 
     AppendMeta m;
     m.units = reinterpret_cast<const AppendUnit *>(dev);
@@ -381,6 +421,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     if (!q || !k_cache || !v_cache || !block_table || !out) return fail(h, SARATHI_EINVAL, "null tensor pointer");
     if (!(sm_scale > 0.0f) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale must be positive and finite");
     if (!workspace) return fail(h, SARATHI_EWORKSPACE, "null workspace");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return fail(h, SARATHI_EWORKSPACE, "workspace is not 256-byte aligned");
     char *ws = static_cast<char *>(workspace);
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -392,18 +433,16 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
         if ((st = ensure_staging(h)) != SARATHI_OK) return st;
         int slot;
-        if ((st = acquire_slot(h, &slot)) != SARATHI_OK) return st;
+        if ((st = acquire_slot(h, s, &slot)) != SARATHI_OK) return st;
         const AttnMetaOffsets o = attn_meta_offsets(h->plan);
         if (o.total > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
         char *host = static_cast<char *>(h->staging[slot]);
         pack_attn_meta(host, h->plan, o);
         dev = ws + h->ws.meta;
         h->resident_ws = nullptr;  // the region no longer holds what an earlier append put there
-        e = hipMemcpyAsync(dev, host, o.total, hipMemcpyHostToDevice, s);
-        if (e != hipSuccess) return hip_fail(h, "hipMemcpyAsync(metadata)", e);
-        e = hipEventRecord(h->staged[slot], s);
-        if (e != hipSuccess) return hip_fail(h, "hipEventRecord", e);
-        h->in_flight[slot] = true;
+        e = (hipError_t)launch_upload(dev, h->staging_dev[slot], o.total, stream);
+        if (e != hipSuccess) return hip_fail(h, "launch upload(metadata)", e);
+        if ((st = release_slot(h, slot, s)) != SARATHI_OK) return st;
     }
     const Plan &pl = h->plan;
     const AttnMetaOffsets mo = attn_meta_offsets(pl);

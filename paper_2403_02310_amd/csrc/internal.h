@@ -160,6 +160,9 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
 // Merges the split tiles named by reduce_units[first .. first+count).
 // Fills `bytes` (a multiple of 4) at `ptr` with zeros by a small kernel (no memset node: callers may capture).
 int launch_zero(void *ptr, size_t bytes, void *stream);
+// Copies `bytes` (rounded up to 16; both buffers hold the rounded size and are 16-byte aligned) from pinned
+// host memory, given by the address the device uses for it, to device memory by a small kernel.
+int launch_upload(void *dst, const void *pinned_src, size_t bytes, void *stream);
 
 int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream);
 

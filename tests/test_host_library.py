@@ -34,7 +34,7 @@ def test_create_rejects_bad_shapes():
         assert e.value.status == status
 
 
-def _call_attention(h, q_start, q_len, ctx_len, num_tokens=None, ws=1, ptr=1, num_pages=100, scale=0.1):
+def _call_attention(h, q_start, q_len, ctx_len, num_tokens=None, ws=256, ptr=1, num_pages=100, scale=0.1):
     qs, ql, cl = (np.ascontiguousarray(a, np.int32) for a in (q_start, q_len, ctx_len))
     i32p = ctypes.POINTER(ctypes.c_int32)
     n = int(ql.sum()) if num_tokens is None else num_tokens
@@ -56,6 +56,7 @@ def test_validation_errors_are_reported_without_a_gpu():
     assert _call_attention(h, [0], [2], [5], num_pages=0) == binding.EINVAL
     assert _call_attention(h, [0], [2], [5], ptr=None) == binding.EINVAL       # null tensor
     assert _call_attention(h, [0], [2], [5], ws=None) == binding.EWORKSPACE
+    assert _call_attention(h, [0], [2], [5], ws=264) == binding.EWORKSPACE      # not 256-byte aligned
     assert _call_attention(h, [0], [2], [5], scale=float("nan")) == binding.EINVAL
     assert _call_attention(h, [0], [2], [5], scale=-1.0) == binding.EINVAL
     assert _call_attention(h, [], [], [], num_tokens=0) == binding.OK          # empty batch: nothing to do
