@@ -371,7 +371,7 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     size_t used = sizeof(AppendUnit) * n_units;
     if (used > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
     // The attention call of this iteration will get the same description: plan it now and let
-    // its metadata ride along in this copy (one host-to-device copy per iteration instead of two).
+    // its metadata ride along in the append launch (no host-to-device copy of its own).
     h->resident_ws = nullptr;
     if (h->opt.plan_at_append) {
         plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
@@ -390,21 +390,25 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
         }
     }
 
+    // One launch: the append blocks read their records straight from the pinned buffer, and a few more blocks of
+    // the same launch move the attention metadata into the workspace (no copy in front of the append kernel).
     char *dev = static_cast<char *>(workspace) + h->ws.meta;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = (hipError_t)launch_upload(dev, h->staging_dev[slot], used, stream);
-    if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "launch upload(metadata)", e); }
-    if ((st = release_slot(h, slot, s)) != SARATHI_OK) return st;
-
     AppendMeta m;
-    m.units = reinterpret_cast<const AppendUnit *>(dev);
+    m.units = static_cast<const AppendUnit *>(h->staging_dev[slot]);
     m.block_table = block_table;
     m.max_blocks = h->cfg.max_blocks_per_seq;
     m.num_units = (int32_t)n_units;
+    if (h->resident_ws) {
+        m.copy_dst = dev + h->resident_attn_off;
+        m.copy_src = static_cast<const char *>(h->staging_dev[slot]) + h->resident_attn_off;
+        m.copy_bytes = used - h->resident_attn_off;
+    }
     const int t0 = timing_begin(h, 0, s);
-    e = (hipError_t)launch_kv_append(h->cfg, m, k_new, v_new, k_cache, v_cache, num_pages, stream);
+    hipError_t e = (hipError_t)launch_kv_append(h->cfg, m, k_new, v_new, k_cache, v_cache, num_pages, stream);
     timing_end(h, 0, t0, s);
-    if (e != hipSuccess) return hip_fail(h, "launch kv_append", e);
+    if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "launch kv_append", e); }
+    if ((st = release_slot(h, slot, s)) != SARATHI_OK) return st;
     return SARATHI_OK;
 }
 

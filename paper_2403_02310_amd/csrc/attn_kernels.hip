@@ -1138,13 +1138,25 @@ struct AppendParams {
     int64_t num_pages;
     int32_t max_blocks;
     int32_t num_kv_heads;
+    // The first copy_blocks blocks move copy_n16 16-byte words from copy_src to copy_dst instead (the attention
+    // metadata of the same iteration, pinned host memory -> workspace, riding in this launch).
+    u32x4 *copy_dst;
+    const u32x4 *copy_src;
+    uint32_t copy_n16;
+    uint32_t copy_blocks;
 };
 
 template <int D>
 __global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
     constexpr int kPieces = D / 8;  // 16-byte pieces of one K row
-    const int unit = (int)(blockIdx.x / (unsigned)p.num_kv_heads);
-    const int h = (int)(blockIdx.x % (unsigned)p.num_kv_heads);
+    if (blockIdx.x < p.copy_blocks) {
+        const uint32_t i = blockIdx.x * D + threadIdx.x;
+        if (i < p.copy_n16) p.copy_dst[i] = p.copy_src[i];
+        return;
+    }
+    const unsigned blk = blockIdx.x - p.copy_blocks;
+    const int unit = (int)(blk / (unsigned)p.num_kv_heads);
+    const int h = (int)(blk % (unsigned)p.num_kv_heads);
     const u32x4 rec = *reinterpret_cast<const u32x4 *>(p.units + unit);
     const int lo = (int)(rec[3] & 0xFFu), hi = (int)(rec[3] >> 8);
     const int n = hi - lo;
@@ -1206,7 +1218,11 @@ int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void 
     p.num_pages = num_pages;
     p.max_blocks = m.max_blocks;
     p.num_kv_heads = cfg.num_kv_heads;
-    const unsigned blocks = (unsigned)m.num_units * (unsigned)cfg.num_kv_heads;
+    p.copy_dst = static_cast<u32x4 *>(m.copy_dst);
+    p.copy_src = static_cast<const u32x4 *>(m.copy_src);
+    p.copy_n16 = (uint32_t)((m.copy_bytes + 15) / 16);
+    p.copy_blocks = (p.copy_n16 + (uint32_t)cfg.head_dim - 1) / (uint32_t)cfg.head_dim;
+    const unsigned blocks = p.copy_blocks + (unsigned)m.num_units * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (cfg.head_dim == 128)
         hipLaunchKernelGGL(kv_append_kernel<128>, dim3(blocks), dim3(128), 0, st, p);

@@ -126,10 +126,15 @@ inline int64_t max_append_units(const sarathi_config &cfg) {
 }
 
 struct AppendMeta {
-    const AppendUnit *units;     // dev [num_units]
+    const AppendUnit *units;     // [num_units]; device memory, or pinned host memory by the address the device uses for it
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
     int32_t num_units;
+    // bytes the launch also moves from copy_src (pinned host memory, device-side address) to copy_dst (device):
+    // rounded up to 16, both 16-byte aligned; 0 = nothing
+    void *copy_dst = nullptr;
+    const void *copy_src = nullptr;
+    size_t copy_bytes = 0;
 };
 
 int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void *k_new, const void *v_new,
