@@ -114,7 +114,8 @@ sarathi_status acquire_slot(sarathi_handle *h, hipStream_t stream, int *slot) {
     return SARATHI_OK;
 }
 
-// After the copy out of `slot` has been enqueued on `stream`.
+// After the launch that reads `slot` has been enqueued on `stream` (or was given up: a half's last slot
+// records the half's event either way, so that the launches out of its other slots stay covered).
 sarathi_status release_slot(sarathi_handle *h, int slot, hipStream_t stream) {
     if (slot % kStagingHalf != kStagingHalf - 1) return SARATHI_OK;
     const int half = slot / kStagingHalf;
@@ -123,6 +124,21 @@ sarathi_status release_slot(sarathi_handle *h, int slot, hipStream_t stream) {
     h->half_pending[half] = true;
     return SARATHI_OK;
 }
+
+// Releases an acquired slot on every path out of the call that holds it.
+struct SlotGuard {
+    sarathi_handle *h;
+    int slot;
+    hipStream_t stream;
+    bool released = false;
+    sarathi_status release() {
+        released = true;
+        return release_slot(h, slot, stream);
+    }
+    ~SlotGuard() {
+        if (!released) (void)release_slot(h, slot, stream);
+    }
+};
 
 constexpr size_t kMaxTimedLaunches = 8192;
 
@@ -356,6 +372,7 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     if ((st = ensure_staging(h)) != SARATHI_OK) return st;
     int slot;
     if ((st = acquire_slot(h, static_cast<hipStream_t>(stream), &slot)) != SARATHI_OK) return st;
+    SlotGuard guard{h, slot, static_cast<hipStream_t>(stream)};
 
     // Metadata: one record per cache page that this iteration writes into.
     AppendUnit *units = static_cast<AppendUnit *>(h->staging[slot]);
@@ -408,7 +425,7 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     hipError_t e = (hipError_t)launch_kv_append(h->cfg, m, k_new, v_new, k_cache, v_cache, num_pages, stream);
     timing_end(h, 0, t0, s);
     if (e != hipSuccess) { h->resident_ws = nullptr; return hip_fail(h, "launch kv_append", e); }
-    if ((st = release_slot(h, slot, s)) != SARATHI_OK) return st;
+    if ((st = guard.release()) != SARATHI_OK) return st;
     return SARATHI_OK;
 }
 
@@ -438,6 +455,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         if ((st = ensure_staging(h)) != SARATHI_OK) return st;
         int slot;
         if ((st = acquire_slot(h, s, &slot)) != SARATHI_OK) return st;
+        SlotGuard guard{h, slot, s};
         const AttnMetaOffsets o = attn_meta_offsets(h->plan);
         if (o.total > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
         char *host = static_cast<char *>(h->staging[slot]);
@@ -446,7 +464,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         h->resident_ws = nullptr;  // the region no longer holds what an earlier append put there
         e = (hipError_t)launch_upload(dev, h->staging_dev[slot], o.total, stream);
         if (e != hipSuccess) return hip_fail(h, "launch upload(metadata)", e);
-        if ((st = release_slot(h, slot, s)) != SARATHI_OK) return st;
+        if ((st = guard.release()) != SARATHI_OK) return st;
     }
     const Plan &pl = h->plan;
     const AttnMetaOffsets mo = attn_meta_offsets(pl);
