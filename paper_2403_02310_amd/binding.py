@@ -200,12 +200,25 @@ class Handle:
             items = list(items)[: info.num_items]
         return info, items
 
+    def _check_block_table(self, block_table, num_seqs: int) -> None:
+        """The C ABI takes a bare pointer and walks it with the handle's row width; a tensor of another width
+        would be read with the wrong stride, so the marshalling layer, which still sees the shape, refuses it."""
+        shape = getattr(block_table, "shape", None)
+        if shape is None:
+            return
+        if len(shape) != 2 or int(shape[1]) != int(self.config.max_blocks_per_seq) or int(shape[0]) < num_seqs:
+            raise ValueError("block_table must be [>= %d, %d] (the handle's max_blocks_per_seq), got %s"
+                             % (num_seqs, self.config.max_blocks_per_seq, tuple(shape)))
+        if hasattr(block_table, "is_contiguous") and not block_table.is_contiguous():
+            raise ValueError("block_table must be contiguous")
+
     def kv_append(self, k_new, v_new, k_cache, v_cache, block_table, q_start, q_len, ctx_len,
                   num_pages: Optional[int] = None, num_tokens: Optional[int] = None, workspace=None, stream=None):
         qs, ql, cl = _i32(q_start), _i32(q_len), _i32(ctx_len)
         n = int(ql.sum()) if num_tokens is None else num_tokens
         pages = int(k_cache.shape[0]) if num_pages is None else num_pages
         ws = workspace if workspace is not None else self.ensure_workspace()
+        self._check_block_table(block_table, len(ql))
         self._check(lib.sarathi_kv_append(self._h, _dev(k_new), _dev(v_new), _dev(k_cache), _dev(v_cache),
                                           _dev(block_table), _ptr(qs), _ptr(ql), _ptr(cl), len(ql), n, pages,
                                           _dev(ws), _stream(stream)))
@@ -217,6 +230,7 @@ class Handle:
         n = int(ql.sum()) if num_tokens is None else num_tokens
         pages = int(k_cache.shape[0]) if num_pages is None else num_pages
         ws = workspace if workspace is not None else self.ensure_workspace()
+        self._check_block_table(block_table, len(ql))
         self._check(lib.sarathi_hybrid_attention(self._h, _dev(q), _dev(k_cache), _dev(v_cache), _dev(block_table),
                                                  _ptr(qs), _ptr(ql), _ptr(cl), len(ql), n, pages, float(sm_scale),
                                                  _dev(out), _dev(ws), _stream(stream)))

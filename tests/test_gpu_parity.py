@@ -246,6 +246,50 @@ def test_run_time_roles_repeat_on_one_workspace(hx):
         np.testing.assert_array_equal(got, first)
 
 
+def test_many_iterations_and_two_streams_on_one_handle(hx):
+    """The per-call metadata travels through a ring of pinned buffers that the launches read directly: forty
+    iterations in a row (the ring wraps twice) with different batches in turn, then the same on two streams used
+    alternately (a stream change inside half a ring takes the library's slow path), every output equal bit for
+    bit to that batch's first result, which is checked against the fp64 checker."""
+    from paper_2403_02310_amd import binding
+    s = SHAPES["gqa4_d128"]
+    batches = [wl._make("ring%d" % i, s, [70 + 9 * i, 1, 1, 5], [300 + 40 * i, 500 - 30 * i, 64 + i, 90], 300 + i, max_blocks=40)
+               for i in range(3)]  # one block-table width: the handle's
+    cap = max(batches, key=lambda b: b.num_tokens)
+    h = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=max(2048, cap.num_tokens), max_seqs=128,
+                       max_blocks_per_seq=40)
+    states, firsts = [], []
+    for b in batches:
+        st = hx.setup_and_run(b, 0x7FC1, handle=h)
+        compare(hx.bf16_tensor_to_f64(st["out"]), oracle.attention_for_batch(b), b.name)
+        k_new, v_new = hx.new_token_kv(b, st["kv_host"])
+        st["k_new"], st["v_new"] = hx.bits_to_device(k_new), hx.bits_to_device(v_new)
+        states.append(st)
+        firsts.append(hx.device_to_bits(st["out"]))
+    outs = []
+    for i in range(40):  # enqueued back to back, no host wait in between
+        b, st = batches[i % 3], states[i % 3]
+        outs.append(hx.run_iteration(h, b, st["k_cache"], st["v_cache"], st["bt"], st["q"], st["k_new"], st["v_new"]))
+    torch.cuda.synchronize()
+    for i, o in enumerate(outs):
+        np.testing.assert_array_equal(hx.device_to_bits(o), firsts[i % 3])
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    outs = []
+    for i in range(24):
+        b, st = batches[i % 3], states[i % 3]
+        sm = streams[(i // 3) % 2]
+        out = torch.empty_like(st["q"])
+        # the two streams share the caches and the workspace: keep their iterations apart
+        sm.wait_stream(streams[1 - (i // 3) % 2])
+        h.kv_append(st["k_new"], st["v_new"], st["k_cache"], st["v_cache"], st["bt"], b.q_start, b.q_len, b.ctx_len, stream=sm)
+        h.hybrid_attention(st["q"], st["k_cache"], st["v_cache"], st["bt"], b.q_start, b.q_len, b.ctx_len, b.sm_scale, out, stream=sm)
+        outs.append(out)
+    torch.cuda.synchronize()
+    for i, o in enumerate(outs):
+        np.testing.assert_array_equal(hx.device_to_bits(o), firsts[i % 3])
+
+
 def test_chunking_invariance_config1(hx):
     """192-token prompt as 1x192, 3x64, 192x1: KV cache bytes identical, outputs within tolerance of the one fp64 result."""
     q_all = wl.normal_bf16((1, 0x51, 99), (192, 4, 64))
