@@ -79,7 +79,13 @@ typedef struct {
 typedef struct sarathi_handle sarathi_handle;
 
 /* Creates host-side state (no device work, usable without a GPU for validation and planning).
- * Pinned staging memory is allocated lazily by the first call that enqueues device work. */
+ * Pinned staging memory is allocated lazily by the first call that enqueues device work: a ring of 16
+ * buffers that hold the per-call metadata and that the launches read directly.  Consequences for callers:
+ * a handle serves one host thread at a time; calls may be enqueued back to back on one stream without any
+ * host wait (the library waits only when it comes round to a buffer whose launch has not run yet); changing
+ * streams between calls is allowed but may make the library wait for the previous stream; the device entry
+ * points must not be recorded into a HIP graph (a replay would read a buffer that later calls have
+ * rewritten).  sarathi_destroy waits for the device before it frees the buffers. */
 sarathi_status sarathi_create(const sarathi_config *config, sarathi_handle **out);
 sarathi_status sarathi_destroy(sarathi_handle *handle);
 
