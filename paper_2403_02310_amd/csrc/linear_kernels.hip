@@ -285,7 +285,9 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
         // a narrow tile next to others of its feature tile shares the weights and is bound by arithmetic (~15 % dearer
         // per token than the 256-token tile); alone it is bound by fetching them.  The 128 x 128 tile is bound by
         // the path global memory -> LDS: ~0.75 us for a quarter of the wide tile's arithmetic.
-        const double stage_us = feature_tile == 128 ? 0.75 : token_tile == 256 ? 1.95 : (t_tiles >= 2 ? 1.12 : 1.3);
+        // The 128 x 64 tile of small batches moves half the weight bytes of the 256-feature tiles per stage.
+        const double stage_us = feature_tile == 128 ? (token_tile == 64 ? 0.7 : 0.75)
+                                                    : token_tile == 256 ? 1.95 : (t_tiles >= 2 ? 1.12 : 1.3);
         for (int64_t s = 1; s <= 16 && (s == 1 || s * 4 <= k_stages); ++s) {
             if (s > 1 && (size_t)(s * per_split_bytes) > workspace_bytes) break;
             const int64_t rounds = (tiles * s + slots - 1) / slots;
@@ -307,8 +309,10 @@ LinearPlan plan_linear(int32_t T, int32_t N, int32_t K, size_t workspace_bytes) 
     // Token tile: the smallest that holds a small batch; from 65 tokens on, 256 tokens per tile halve the
     // operand traffic per MFMA, 128 waste less of a ragged batch and give twice the workgroups, and 128 x 128
     // tiles give four times the workgroups to a matrix that is too small to fill the chip otherwise.
-    if (T <= 32) consider(256, 32);
-    else if (T <= 64) consider(256, 64);
+    // Small batches are bound by fetching the weights: 128-feature tiles give a large matrix enough workgroups
+    // to fill the chip without cutting k (no partial tiles, no second kernel).
+    if (T <= 32) { consider(256, 32); consider(128, 64); }
+    else if (T <= 64) { consider(256, 64); consider(128, 64); }
     else {
         consider(256, 256);
         consider(256, 128);
@@ -330,8 +334,10 @@ int launch_linear(const LinearPlan &pl, const void *x, const void *w, void *y, i
     const int64_t blocks = kLinXcds * n_rounds * pl.t_tiles * pl.splits;
     if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidValue;  // more workgroups than a grid holds
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // LDS: 4 x 32 KiB, 2 x 64 KiB, 3 x 48 KiB, 3 x 40 KiB, 4 x 36 KiB
-    if (pl.feature_tile == 128)
+    // LDS: 6 x 24 KiB, 4 x 32 KiB, 2 x 64 KiB, 3 x 48 KiB, 3 x 40 KiB, 4 x 36 KiB
+    if (pl.feature_tile == 128 && pl.token_tile == 64)
+        hipLaunchKernelGGL((linear_kernel<64, 2, 6, kLinStageK, 128>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
+    else if (pl.feature_tile == 128)
         hipLaunchKernelGGL((linear_kernel<128, 2, 4, kLinStageK, 128>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);
     else if (pl.token_tile == 256)
         hipLaunchKernelGGL((linear_kernel<256, 2, 2>), dim3((unsigned)blocks), dim3(kLinThreads), 0, st, p);

@@ -111,8 +111,10 @@ def test_model_shapes_sampled(hx):
     rng = np.random.default_rng(17)
     # ... and Falcon-180B's QKV (a feature count that is not a multiple of the 256-feature tile) and attention
     # output projection (58 stages of 64 k) under TP4, LLaMA2-70B's QKV under TP4 at a decode-sized batch
+    # ... and two decode-sized batches on wide matrices, which take the 128 x 64 tile (enough workgroups without
+    # cutting k): Mistral-7B's feed-forward up projection, and a ragged 33-token batch on a shorter k
     for (T, N, K) in [(128, 28672, 4096), (2048, 4096, 14336), (640, 6144, 4096), (200, 3968, 14848), (2048, 14848, 3712),
-                      (48, 2560, 8192)]:
+                      (48, 2560, 8192), (16, 28672, 4096), (33, 28672, 512)]:
         rows = sorted(set([0, T - 1, 127 % T, 128 % T] + rng.integers(0, T, 12).tolist()))
         cols = sorted(set([0, N - 1, 127, 128, 1023, 1024] + rng.integers(0, N, 40).tolist()))
         run(hx, T, N, K, seed=21, rows=rows, cols=cols)
