@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the attention kernels (fetch + write), from two `rocprofv3 --pmc` runs
 # (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read on a plain copy of known size;
 # the runs and the scaling are recorded in profiles/ (attention_c2_mistral_hybrid.md and its siblings).
-MEASURED_TRAFFIC_BYTES = {"c2": 604.3e6, "c3": 1480.8e6, "c4": 5015.9e6, "c4_chunks": 344.4e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 606.4e6, "c3": 1480.8e6, "c4": 5015.9e6, "c4_chunks": 344.4e6}
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published

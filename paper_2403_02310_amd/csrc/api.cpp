@@ -488,9 +488,15 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     // the decodes need to stream their keys and values (~5 bytes/ps).
     const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
     const double wave_us = (double)pl.wave_keys * h->cfg.num_kv_heads * h->cfg.head_dim * 4.0 / 5.0e6;
-    // The streaming hint pays on decode streams (+2 to +7 %) and costs 1 to 3 % when chunk blocks that
-    // matter run beside them (their K/V tiles then miss more often).
-    m.stream_kv = h->opt.stream_kv >= 0 ? (int32_t)h->opt.stream_kv : (chunk_us < 0.1 * wave_us ? 1 : 0);
+    // The streaming hint pays on decode streams (+2 to +7 % without chunk work) and where the batch's longest
+    // chunk unit runs about as long as the decodes stream, because the chunk blocks, whose K/V tiles then stay in
+    // L2, are what the launch waits for (+1 to +3 % on a 512-token chunk behind a 3000-token prefix next to 64
+    // decodes); it costs 2 to 3 % where the decodes are the last to finish next to chunk work that matters (the
+    // same batch with a 1400-token prefix; the long-context batch).  A chunk block's 32-key step takes ~0.9 us
+    // next to streaming decodes.
+    const double chunk_tail_us = (double)pl.longest_tile_unit_steps * 0.9;
+    const bool stream_auto = chunk_us < 0.1 * wave_us || chunk_tail_us > 0.7 * wave_us;
+    m.stream_kv = h->opt.stream_kv >= 0 ? (int32_t)h->opt.stream_kv : (stream_auto ? 1 : 0);
     // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
     // has both they run side by side: the chunk kernel is forked onto a second stream, where the
     // merge of its own split tiles follows it (hidden behind the longer wave kernel).

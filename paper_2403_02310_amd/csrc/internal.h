@@ -65,6 +65,7 @@ struct Plan {
     int32_t split_keys = 0;
     int32_t tile_split_keys = 0;
     int64_t tile_unit_steps = 0;      // 32-key steps summed over the chunk-tile units
+    int32_t longest_tile_unit_steps = 0;  // 32-key steps of the longest chunk-tile unit
     int64_t wave_keys = 0;            // keys summed over the wave tiles
 };
 
@@ -92,7 +93,8 @@ struct Options {
                                     // second stream next to the wave kernel, 2 = one launch holding both kinds of block
     int64_t window = 0;             // sliding-window attention: a query sees its last `window` keys (itself included); 0 = all
     int64_t stream_kv = -1;         // decode K/V loads carry the streaming (non-temporal) hint: -1 = when the batch's chunk
-                                    // work is absent or small next to its decode streams, 0 = never, 1 = always
+                                    // work is absent or small next to its decode streams, or its longest chunk unit
+                                    // runs about as long as they do; 0 = never, 1 = always
     int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
                                     // a compute unit holds at most one chunk block while decode work remains
                                     // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)

@@ -249,6 +249,11 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     plan.tile_unit_steps = 0;
     for (size_t ti = 0; ti < n_chunk_tiles; ++ti)
         plan.tile_unit_steps += ceil_div(plan.tiles[ti].n_keys - plan.tiles[ti].key_lo, kTileKeys) + plan.tiles[ti].n_splits - 1;
+    plan.longest_tile_unit_steps = 0;  // units are sorted longest first
+    if (plan.num_tile_units > 0) {
+        const uint32_t u = plan.units[0];
+        plan.longest_tile_unit_steps = steps_of_split(plan.tiles[u & ((1u << kUnitTileBits) - 1)], (int32_t)(u >> kUnitTileBits));
+    }
     plan.wave_keys = keys_of_kind[kKindWave];
     emit_units(plan, n_chunk_tiles, plan.tiles.size(), wave_split, scratch, bucket);
 }
