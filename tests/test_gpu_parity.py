@@ -290,6 +290,35 @@ def test_many_iterations_and_two_streams_on_one_handle(hx):
         np.testing.assert_array_equal(hx.device_to_bits(o), firsts[i % 3])
 
 
+def test_kernel_timing_brackets_every_nth_launch(hx):
+    """Options time_kernels / time_every: with every 4th attention launch bracketed, 8 iterations report 2 timed
+    launches with a positive duration, and the outputs do not depend on the instrumentation."""
+    b = wl.random_hybrid(21, wl.AttnShape(8, 2, 128), n_chunks=1, n_decodes=6, max_chunk=80, max_ctx=700)
+    h = hx.make_handle(b)
+    st = hx.setup_and_run(b, 0x7FC1, handle=h)
+    first = hx.device_to_bits(st["out"])
+    k_new, v_new = hx.new_token_kv(b, st["kv_host"])
+    k_new, v_new = hx.bits_to_device(k_new), hx.bits_to_device(v_new)
+    h.set_option("time_kernels", 1)
+    h.set_option("time_every", 4)
+    h.kernel_times()
+    for _ in range(8):
+        out = hx.run_iteration(h, b, st["k_cache"], st["v_cache"], st["bt"], st["q"], k_new, v_new)
+    torch.cuda.synchronize()
+    kt = h.kernel_times()
+    assert kt.attention_launches == 2 and kt.attention_ms > 0.0 and kt.append_launches == 0
+    np.testing.assert_array_equal(hx.device_to_bits(out), first)
+    h.set_option("time_kernels", 2)
+    h.set_option("time_every", 1)
+    for _ in range(3):
+        hx.run_iteration(h, b, st["k_cache"], st["v_cache"], st["bt"], st["q"], k_new, v_new)
+    torch.cuda.synchronize()
+    kt = h.kernel_times()
+    assert kt.attention_launches == 3 and kt.append_launches == 3
+    with pytest.raises(Exception):
+        h.set_option("time_every", 0)
+
+
 def test_chunking_invariance_config1(hx):
     """192-token prompt as 1x192, 3x64, 192x1: KV cache bytes identical, outputs within tolerance of the one fp64 result."""
     q_all = wl.normal_bf16((1, 0x51, 99), (192, 4, 64))
