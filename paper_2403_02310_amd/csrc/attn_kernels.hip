@@ -1160,12 +1160,13 @@ __global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
     const u32x4 rec = *reinterpret_cast<const u32x4 *>(p.units + unit);
     const int lo = (int)(rec[3] & 0xFFu), hi = (int)(rec[3] >> 8);
     const int n = hi - lo;
-    const int64_t page = p.block_table[(int64_t)(int)rec[0] * p.max_blocks + (int)rec[1]];
-    if (page < 0 || page >= p.num_pages) return;  // a corrupt table entry must not become a wild store
     const int64_t row_stride = (int64_t)p.num_kv_heads * D;
     const int64_t src = ((int64_t)(int)rec[2] * p.num_kv_heads + h) * D;
-    const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
     const int tid = (int)threadIdx.x;
+    // The block-table entry and the rows to move depend on the record only: all of these loads are issued
+    // before the first is waited for (the table entry decides where the rows go, and whether they go at all).
+    const int32_t *entry = p.block_table + (int64_t)(int)rec[0] * p.max_blocks + (int)rec[1];
+    const int64_t page = *entry;
 
     // V: gather first (all loads in flight before any store)
     const uint16_t *vsrc = p.v_new + src + tid;
@@ -1174,15 +1175,24 @@ __global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
     for (int i = 0; i < kPageSize; ++i) x[i] = (i < n) ? vsrc[i * row_stride] : (uint16_t)0;
 
     // K: n rows of D channels, destination contiguous
+    constexpr int kRounds = (kPageSize * kPieces) / D;
     const uint16_t *ksrc = p.k_new + src;
-    uint16_t *kdst = p.k_cache + head_base + (int64_t)lo * D;
+    u32x4 krow[kRounds];
 #pragma unroll
-    for (int r = 0; r < (kPageSize * kPieces) / D; ++r) {
+    for (int r = 0; r < kRounds; ++r) {
         const int j = tid + r * D;
         const int i = j / kPieces, piece = j % kPieces;
-        if (i < n)
-            *reinterpret_cast<u32x4 *>(kdst + i * D + piece * 8) =
-                *reinterpret_cast<const u32x4 *>(ksrc + i * row_stride + piece * 8);
+        krow[r] = (i < n) ? *reinterpret_cast<const u32x4 *>(ksrc + i * row_stride + piece * 8) : u32x4{0, 0, 0, 0};
+    }
+
+    if (page < 0 || page >= p.num_pages) return;  // a corrupt table entry must not become a wild store
+    const int64_t head_base = (page * p.num_kv_heads + h) * (int64_t)(kPageSize * D);
+    uint16_t *kdst = p.k_cache + head_base + (int64_t)lo * D;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int j = tid + r * D;
+        const int i = j / kPieces, piece = j % kPieces;
+        if (i < n) *reinterpret_cast<u32x4 *>(kdst + i * D + piece * 8) = krow[r];
     }
 
     uint16_t *vdst = p.v_cache + head_base + (int64_t)tid * kPageSize;
