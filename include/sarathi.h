@@ -90,7 +90,10 @@ sarathi_status sarathi_create(const sarathi_config *config, sarathi_handle **out
 sarathi_status sarathi_destroy(sarathi_handle *handle);
 
 /* Bytes of device scratch the caller must pass as `workspace` (256-byte aligned) to the two
- * device entry points: batch metadata, the work lists and the split-KV partial results. */
+ * device entry points: batch metadata, the work lists, scheduling words and the split-KV partial results.
+ * Nothing is expected of its contents (no region has to be zero on entry).  Between a sarathi_kv_append and the
+ * sarathi_hybrid_attention of the same iteration the metadata region holds that iteration's plan: do not
+ * overwrite it in between (the attention call would read a stale plan). */
 size_t sarathi_workspace_bytes(const sarathi_handle *handle);
 
 /* Text of the last error on this handle (includes hipGetErrorString where relevant). */
@@ -165,8 +168,10 @@ sarathi_status sarathi_kv_append(sarathi_handle *handle,
  * Prefill-chunk rows and decode rows run in the same launch; long key ranges are split
  * into independent pieces whose partial (max, sum, unnormalised output) triples are merged
  * in a fixed order by a second small kernel, so results are bitwise reproducible run to
- * run and do not depend on which physical pages hold the data.  A call enqueues one
- * host-to-device copy of the batch metadata and one or two kernels.
+ * run and do not depend on which physical pages hold the data.  A call enqueues kernels only: a small
+ * one that moves the batch metadata from the handle's pinned buffer into the workspace (not needed when the
+ * sarathi_kv_append of the same iteration has already brought it), a fill of the scheduling words when blocks
+ * take their role at run time, the attention launch, and the merge when a key range was cut.
  */
 sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
                                         const void *q,

@@ -45,8 +45,6 @@ struct sarathi_handle {
     // call gets the same description, so its plan rides along in the append's copy.  Valid while
     // `resident_*` describe what the metadata region of `resident_ws` holds.
     void *resident_ws = nullptr;
-    // workspace whose scheduling words this handle has zeroed
-    const void *sched_ws = nullptr;
     void *resident_stream = nullptr;
     std::vector<int32_t> resident_desc;  // q_len | ctx_len of the planned batch
     uint64_t resident_opt_version = 0;
@@ -186,6 +184,96 @@ bool resident_plan_matches(const sarathi_handle *h, const int32_t *q_len, const 
     if (h->resident_desc.size() != 2 * (size_t)n) return false;
     return std::memcmp(h->resident_desc.data(), q_len, sizeof(int32_t) * (size_t)n) == 0 &&
            std::memcmp(h->resident_desc.data() + n, ctx_len, sizeof(int32_t) * (size_t)n) == 0;
+}
+
+// Enqueues the attention launch (and the merge of split tiles) for h->plan, whose packed metadata is at `dev`.
+// `instrumented` = false: the allocation-free entry point, which records no timing events and never forks a
+// second stream (both create runtime objects on first use).
+sarathi_status enqueue_attention(sarathi_handle *h, char *dev, float *part_ml, float *part_o, int32_t *sched,
+                                 const int32_t *block_table, const void *q, const void *k_cache, const void *v_cache,
+                                 int64_t num_pages, float sm_scale, void *out, hipStream_t s, bool instrumented) {
+    const Plan &pl = h->plan;
+    const AttnMetaOffsets mo = attn_meta_offsets(pl);
+    const size_t units_off = mo.units, reduce_off = mo.reduce;
+    void *stream = static_cast<void *>(s);
+    hipError_t e;
+
+    AttnMeta m;
+    m.tiles = reinterpret_cast<const TileDesc *>(dev);
+    m.units = reinterpret_cast<const uint32_t *>(dev + units_off);
+    m.num_tile_units = pl.num_tile_units;
+    m.num_units = (int32_t)pl.units.size();
+    m.block_table = block_table;
+    m.max_blocks = h->cfg.max_blocks_per_seq;
+    m.reduce_units = reinterpret_cast<const uint32_t *>(dev + reduce_off);
+    m.num_reduce_units = (int32_t)pl.reduce_units.size();
+    m.num_tile_reduce_units = pl.num_tile_reduce_units;
+    m.part_ml = part_ml;
+    m.part_o = part_o;
+    m.sched = sched;
+    m.window = (int32_t)h->opt.window;
+    // Rough durations: chunk work with one block per compute unit (~0.65 us per 32-key step), and the time
+    // the decodes need to stream their keys and values (~5 bytes/ps).
+    const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
+    const double wave_us = (double)pl.wave_keys * h->cfg.num_kv_heads * h->cfg.head_dim * 4.0 / 5.0e6;
+    // The streaming hint pays on decode streams (+2 to +7 % without chunk work) and where the batch's longest
+    // chunk unit runs about as long as the decodes stream, because the chunk blocks, whose K/V tiles then stay in
+    // L2, are what the launch waits for (+1 to +3 % on a 512-token chunk behind a 3000-token prefix next to 64
+    // decodes); it costs 2 to 3 % where the decodes are the last to finish next to chunk work that matters (the
+    // same batch with a 1400-token prefix; the long-context batch).  A chunk block's 32-key step takes ~0.9 us
+    // next to streaming decodes.
+    const double chunk_tail_us = (double)pl.longest_tile_unit_steps * 0.9;
+    const bool stream_auto = chunk_us < 0.1 * wave_us || chunk_tail_us > 0.7 * wave_us;
+    m.stream_kv = h->opt.stream_kv >= 0 ? (int32_t)h->opt.stream_kv : (stream_auto ? 1 : 0);
+    // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
+    // has both they run side by side: the chunk kernel is forked onto a second stream, where the
+    // merge of its own split tiles follows it (hidden behind the longer wave kernel).
+    const bool both = pl.num_tile_units > 0 && (int32_t)pl.units.size() > pl.num_tile_units;
+    const bool fork = both && h->opt.interleave == 1 && instrumented;
+    if (fork && !h->side_stream) {
+        e = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) return hip_fail(h, "hipStreamCreate(side)", e);
+        e = hipEventCreateWithFlags(&h->fork_event, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&h->join_event, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(h, "hipEventCreate(fork/join)", e);
+    }
+    int32_t merged_on_side = 0;
+    const int t1 = instrumented ? timing_begin(h, 1, s) : -1;
+    if (fork) {
+        e = hipEventRecord(h->fork_event, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(h->side_stream, h->fork_event, 0);
+        if (e != hipSuccess) return hip_fail(h, "fork to side stream", e);
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1, h->side_stream);
+        if (e == hipSuccess) e = (hipError_t)launch_reduce(h->cfg, m, out, 0, m.num_tile_reduce_units, h->side_stream);
+        merged_on_side = m.num_tile_reduce_units;
+        if (e == hipSuccess) e = hipEventRecord(h->join_event, h->side_stream);
+        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, h->join_event, 0);
+    } else if (both && (h->opt.interleave == 2 || !instrumented)) {
+        // Run-time roles pay (a few atomics per block) when chunk blocks would otherwise pile up two
+        // to a compute unit for a good part of the launch: more chunk blocks than units, and chunk
+        // work that is not small next to the time the decodes need to stream.
+        const bool many_chunk_blocks = (int64_t)pl.num_tile_units * h->cfg.num_kv_heads > kChunkBlocksForRoles &&
+                                       chunk_us > 0.25 * wave_us;
+        const bool roles = h->cfg.num_kv_heads <= kSchedMaxKvHeads &&
+                           (h->opt.resident_chunks == 1 || (h->opt.resident_chunks < 0 && many_chunk_blocks));
+        if (roles) {  // the scheduling words start at zero, whatever the last user of the memory left there
+            e = (hipError_t)launch_zero(m.sched, kSchedBytes, stream);
+            if (e != hipSuccess) return hip_fail(h, "launch zero fill", e);
+        }
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, roles ? 5 : 4, stream);
+    } else {
+        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, stream);
+    }
+    timing_end(h, 1, t1, s);
+    if (e != hipSuccess) return hip_fail(h, "launch attention", e);
+    if (m.num_reduce_units > merged_on_side) {
+        const int t2 = instrumented ? timing_begin(h, 2, s) : -1;
+        e = (hipError_t)launch_reduce(h->cfg, m, out, merged_on_side, m.num_reduce_units - merged_on_side, stream);
+        timing_end(h, 2, t2, s);
+        if (e != hipSuccess) return hip_fail(h, "launch split-KV merge", e);
+    }
+    return SARATHI_OK;
 }
 
 }  // namespace
@@ -466,87 +554,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         if (e != hipSuccess) return hip_fail(h, "launch upload(metadata)", e);
         if ((st = guard.release()) != SARATHI_OK) return st;
     }
-    const Plan &pl = h->plan;
-    const AttnMetaOffsets mo = attn_meta_offsets(pl);
-    const size_t units_off = mo.units, reduce_off = mo.reduce;
-
-    AttnMeta m;
-    m.tiles = reinterpret_cast<const TileDesc *>(dev);
-    m.units = reinterpret_cast<const uint32_t *>(dev + units_off);
-    m.num_tile_units = pl.num_tile_units;
-    m.num_units = (int32_t)pl.units.size();
-    m.block_table = block_table;
-    m.max_blocks = h->cfg.max_blocks_per_seq;
-    m.reduce_units = reinterpret_cast<const uint32_t *>(dev + reduce_off);
-    m.num_reduce_units = (int32_t)pl.reduce_units.size();
-    m.num_tile_reduce_units = pl.num_tile_reduce_units;
-    m.part_ml = reinterpret_cast<float *>(ws + h->ws.part_ml);
-    m.part_o = reinterpret_cast<float *>(ws + h->ws.part_o);
-    m.sched = reinterpret_cast<int32_t *>(ws + h->ws.sched);
-    m.window = (int32_t)h->opt.window;
-    // Rough durations: chunk work with one block per compute unit (~0.65 us per 32-key step), and the time
-    // the decodes need to stream their keys and values (~5 bytes/ps).
-    const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
-    const double wave_us = (double)pl.wave_keys * h->cfg.num_kv_heads * h->cfg.head_dim * 4.0 / 5.0e6;
-    // The streaming hint pays on decode streams (+2 to +7 % without chunk work) and where the batch's longest
-    // chunk unit runs about as long as the decodes stream, because the chunk blocks, whose K/V tiles then stay in
-    // L2, are what the launch waits for (+1 to +3 % on a 512-token chunk behind a 3000-token prefix next to 64
-    // decodes); it costs 2 to 3 % where the decodes are the last to finish next to chunk work that matters (the
-    // same batch with a 1400-token prefix; the long-context batch).  A chunk block's 32-key step takes ~0.9 us
-    // next to streaming decodes.
-    const double chunk_tail_us = (double)pl.longest_tile_unit_steps * 0.9;
-    const bool stream_auto = chunk_us < 0.1 * wave_us || chunk_tail_us > 0.7 * wave_us;
-    m.stream_kv = h->opt.stream_kv >= 0 ? (int32_t)h->opt.stream_kv : (stream_auto ? 1 : 0);
-    // Chunk tiles (compute-bound) and wave tiles (memory-bound) are two kernels; when the batch
-    // has both they run side by side: the chunk kernel is forked onto a second stream, where the
-    // merge of its own split tiles follows it (hidden behind the longer wave kernel).
-    const bool both = pl.num_tile_units > 0 && (int32_t)pl.units.size() > pl.num_tile_units;
-    const bool fork = both && h->opt.interleave == 1;
-    if (fork && !h->side_stream) {
-        e = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking);
-        if (e != hipSuccess) return hip_fail(h, "hipStreamCreate(side)", e);
-        e = hipEventCreateWithFlags(&h->fork_event, hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&h->join_event, hipEventDisableTiming);
-        if (e != hipSuccess) return hip_fail(h, "hipEventCreate(fork/join)", e);
-    }
-    int32_t merged_on_side = 0;
-    const int t1 = timing_begin(h, 1, s);
-    if (fork) {
-        e = hipEventRecord(h->fork_event, s);
-        if (e == hipSuccess) e = hipStreamWaitEvent(h->side_stream, h->fork_event, 0);
-        if (e != hipSuccess) return hip_fail(h, "fork to side stream", e);
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 1, h->side_stream);
-        if (e == hipSuccess) e = (hipError_t)launch_reduce(h->cfg, m, out, 0, m.num_tile_reduce_units, h->side_stream);
-        merged_on_side = m.num_tile_reduce_units;
-        if (e == hipSuccess) e = hipEventRecord(h->join_event, h->side_stream);
-        if (e == hipSuccess) e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 2, stream);
-        if (e == hipSuccess) e = hipStreamWaitEvent(s, h->join_event, 0);
-    } else if (both && h->opt.interleave == 2) {
-        // Run-time roles pay (a few atomics per block) when chunk blocks would otherwise pile up two
-        // to a compute unit for a good part of the launch: more chunk blocks than units, and chunk
-        // work that is not small next to the time the decodes need to stream.
-        const bool many_chunk_blocks = (int64_t)pl.num_tile_units * h->cfg.num_kv_heads > kChunkBlocksForRoles &&
-                                       chunk_us > 0.25 * wave_us;
-        const bool roles = h->cfg.num_kv_heads <= kSchedMaxKvHeads &&
-                           (h->opt.resident_chunks == 1 || (h->opt.resident_chunks < 0 && many_chunk_blocks));
-        if (roles) {
-            if (h->sched_ws != workspace) {  // first use of this workspace: the scheduling words start at zero
-                e = (hipError_t)launch_zero(m.sched, kSchedBytes, stream);
-                if (e != hipSuccess) return hip_fail(h, "launch zero fill", e);
-                h->sched_ws = workspace;
-            }
-        }
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, roles ? 5 : 4, stream);
-    } else {
-        e = (hipError_t)launch_attention(h->cfg, m, q, k_cache, v_cache, num_pages, sm_scale, out, 3, stream);
-    }
-    timing_end(h, 1, t1, s);
-    if (e != hipSuccess) return hip_fail(h, "launch attention", e);
-    if (m.num_reduce_units > merged_on_side) {
-        const int t2 = timing_begin(h, 2, s);
-        e = (hipError_t)launch_reduce(h->cfg, m, out, merged_on_side, m.num_reduce_units - merged_on_side, stream);
-        timing_end(h, 2, t2, s);
-        if (e != hipSuccess) return hip_fail(h, "launch split-KV merge", e);
-    }
-    return SARATHI_OK;
+    return enqueue_attention(h, dev, reinterpret_cast<float *>(ws + h->ws.part_ml), reinterpret_cast<float *>(ws + h->ws.part_o),
+                             reinterpret_cast<int32_t *>(ws + h->ws.sched), block_table, q, k_cache, v_cache, num_pages, sm_scale,
+                             out, s, /*instrumented=*/true);
 }

@@ -986,9 +986,9 @@ __global__ __launch_bounds__(256, 2) void attn_wave_kernel(AttnParams p) {
 // and otherwise takes wave tiles; work is handed out by per-KV-head queue heads (atomic adds), each
 // kind longest first, and a block whose preferred queue is empty takes from the other one.  The grid
 // has exactly one block per work item and KV head, so the second queue cannot be empty too.  All
-// atomics are relaxed: they only hand out indices into the read-only plan.  Every block counts itself
-// in after it has taken its item, and the block that completes the count of its KV head puts that
-// head's words back to zero when it ends, so a launch leaves the scheduling words as it found them.
+// atomics are relaxed: they only hand out indices into the read-only plan.  The host clears the
+// scheduling words with a small fill kernel in front of every such launch, so nothing depends on what
+// an earlier launch (or anybody else) left in them.
 template <int D, bool ROLES, bool STREAM>
 __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ChunkSmem<D>::kTotalElems];
@@ -997,7 +997,7 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
     constexpr uint32_t kTileMask = (1u << kUnitTileBits) - 1;
     const int n_wave_blocks = p.num_units - p.num_tile_units;
     bool chunk_role = blk < p.num_tile_units;
-    __shared__ int32_t role[4];  // kind, index, "this block set its compute unit's flag", "last block of its KV head to take an item"
+    __shared__ int32_t role[3];  // kind, index, "this block set its compute unit's flag"
     // compute unit, shader array and shader engine ids (bits 8..15 of HW_ID) and the XCC id
     auto my_cu_flag = [&]() -> int32_t * {
         const uint32_t hw = __builtin_amdgcn_s_getreg((7 << 11) | (8 << 6) | 4);
@@ -1019,11 +1019,8 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
                 idx = __hip_atomic_fetch_add(heads + kind * kSchedMaxKvHeads + kvh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (idx >= (kind ? p.num_tile_units : n_wave_blocks)) idx = -1;  // cannot happen: one block per item
             }
-            // the items above are taken (their results were waited for) before this block counts itself in
-            const int arrived = __hip_atomic_fetch_add(heads + 2 * kSchedMaxKvHeads + kvh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             role[0] = kind;
             role[1] = idx;
-            role[3] = arrived == p.num_tile_units + n_wave_blocks - 1;
         }
         __syncthreads();
         chunk_role = role[0] != 0;
@@ -1041,15 +1038,8 @@ __global__ __launch_bounds__(256, 2) void attn_hybrid_kernel(AttnParams p) {
             wave16_path<D, STREAM>(p, p.tiles[u & kTileMask], (int)(u >> kUnitTileBits), kvh, reinterpret_cast<float *>(smem));
         }
     }
-    if (ROLES && threadIdx.x == 0) {
-        if (role[2]) __hip_atomic_store(my_cu_flag(), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (role[3]) {  // every block of this KV head has taken its item: nobody reads these words again
-            int32_t *heads = p.sched + kSchedCuSlots;
-            __hip_atomic_store(heads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(heads + kSchedMaxKvHeads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(heads + 2 * kSchedMaxKvHeads + kvh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
+    // the compute unit is free for another chunk block
+    if (ROLES && threadIdx.x == 0 && role[2]) __hip_atomic_store(my_cu_flag(), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Per-call metadata, host -> device: a kernel that reads the pinned host buffer itself.  The runtime's copy

@@ -20,11 +20,10 @@ constexpr int kKindWave = 0;
 constexpr int kKindTile = 1;
 // Scheduling words of the one-launch hybrid kernel when blocks pick their role at run time:
 // one "a chunk block lives here" flag per compute unit (indexed by hardware ids), then per-KV-head
-// queue heads [kind][kv head] and arrival counts [kv head].  All words are zero between launches:
-// a launch leaves them as it found them.
+// queue heads [kind][kv head].  The host zeroes them (fill kernel) in front of every launch that uses them.
 constexpr int kSchedCuSlots = 4096;
 constexpr int kSchedMaxKvHeads = 128;
-constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 3 * kSchedMaxKvHeads);
+constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 2 * kSchedMaxKvHeads);
 constexpr int kChunkBlocksForRoles = 256;   // one per compute unit
 
 // One tile of query columns of one sequence.  A "column" is one (query row, query head inside
@@ -73,7 +72,7 @@ struct Plan {
 struct WorkspaceLayout {
     size_t meta;          // per-call metadata, packed: sequence arrays + hints (append) or tile descriptors + units (attention)
     size_t meta_bytes;
-    size_t sched;         // int32 [kSchedCuSlots + 3*kSchedMaxKvHeads], zero between launches
+    size_t sched;         // int32 [kSchedCuSlots + 2*kSchedMaxKvHeads], zeroed by the host before each launch that uses it
     size_t part_ml;       // float [max_part_rows][Hkv][2]
     size_t part_o;        // float [max_part_rows][Hkv][head_dim]
     size_t total;
@@ -160,7 +159,7 @@ struct AttnMeta {
 };
 
 // which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch,
-// 5 = one launch whose blocks take their role at run time (needs m.sched zeroed once, see launch_zero)
+// 5 = one launch whose blocks take their role at run time (needs m.sched zeroed, see launch_zero)
 int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q, const void *k_cache,
                      const void *v_cache, int64_t num_pages, float sm_scale, void *out, int which, void *stream);
 

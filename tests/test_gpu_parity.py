@@ -246,6 +246,32 @@ def test_run_time_roles_repeat_on_one_workspace(hx):
         np.testing.assert_array_equal(got, first)
 
 
+def test_run_time_roles_do_not_depend_on_what_the_workspace_held(hx):
+    """The scheduling words of the run-time role assignment live in the caller's workspace; whatever an earlier
+    user of that memory left there (all-ones bytes here, then the leftovers of a launch, then all-ones again)
+    must not change the result."""
+    s = SHAPES["gqa4_d128"]
+    b = wl._make("roles_dirty", s, [200, 150, 1, 1, 1, 9, 1], [900, 150, 700, 33, 1200, 64, 300], 84)
+    h = hx.make_handle(b)
+    h.set_option("resident_chunks", 1)
+    h.set_option("tile_split_keys", 256)
+    ws = h.ensure_workspace()
+    ws.fill_(0xFF)
+    torch.cuda.synchronize()
+    st = hx.setup_and_run(b, 0x7FC1, handle=h)
+    ref = oracle.attention_for_batch(b)
+    first = hx.bf16_tensor_to_f64(st["out"])
+    compare(first, ref, "roles on a workspace of 0xFF bytes")
+    k_new, v_new = hx.new_token_kv(b, st["kv_host"])
+    k_new, v_new = hx.bits_to_device(k_new), hx.bits_to_device(v_new)
+    for i in range(2):
+        if i == 1:
+            ws.fill_(0xFF)
+        out = hx.run_iteration(h, b, st["k_cache"], st["v_cache"], st["bt"], st["q"], k_new, v_new)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(hx.bf16_tensor_to_f64(out), first)
+
+
 def test_many_iterations_and_two_streams_on_one_handle(hx):
     """The per-call metadata travels through a ring of pinned buffers that the launches read directly: forty
     iterations in a row (the ring wraps twice) with different batches in turn, then the same on two streams used
