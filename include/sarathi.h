@@ -182,6 +182,33 @@ sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
                                         float sm_scale, void *out,
                                         void *workspace, void *stream);
 
+/*
+ * The same attention for callers that cannot allocate device memory or hand a workspace over: code that runs
+ * under HIP stream capture, tight serving loops, harnesses that forbid hipMalloc.  Identical to
+ * sarathi_hybrid_attention except that it takes no workspace: the batch metadata, the scheduling words and the
+ * split-KV partial rows live in a fixed array of about 16.6 MiB inside the library's device image (each GPU the
+ * library runs on holds one copy until the process ends), and the metadata reaches the device in the arguments of
+ * small kernels (3,840 bytes per launch) instead of through the handle's pinned buffers.  The call allocates
+ * nothing (no hipMalloc / hipHostMalloc / hipFree, no stream or event creation) and enqueues kernels only; it
+ * records no timing events ("time_kernels" is ignored) and treats option "interleave" = 1 as 2.
+ *
+ * Limits: the packed plan (48 bytes per tile of 16 decode columns or 128 chunk columns, 4 bytes per work item)
+ * must fit into 64 KiB, else SARATHI_ECAPACITY (roughly 1,200 sequences); 16 MiB of partial rows (4,096 rows at
+ * 8 KV heads x 128 channels; key ranges are cut less finely when that is short, never refused);
+ * num_kv_heads * head_dim * 4 bytes per partial row must leave room for 256 rows, else SARATHI_ECAPACITY.
+ * Every call on a GPU shares that GPU's array: two calls that overlap in time on one GPU (two streams, two
+ * handles, two threads) race; calls ordered by one stream are safe.  What must start at zero (the scheduling
+ * words) is cleared by a fill kernel inside the call.  Results agree with sarathi_hybrid_attention's within the
+ * attention tolerance, and bit for bit when no key range is cut differently.
+ */
+sarathi_status sarathi_hybrid_attention_noalloc(sarathi_handle *handle,
+                                                const void *q,
+                                                const void *k_cache, const void *v_cache,
+                                                const int32_t *block_table,
+                                                const int32_t *q_start, const int32_t *q_len, const int32_t *ctx_len,
+                                                int32_t num_seqs, int32_t num_tokens, int64_t num_pages,
+                                                float sm_scale, void *out, void *stream);
+
 /* Host-only view of the work decomposition sarathi_hybrid_attention would launch for this
  * description (no device work).  For tests and for sizing studies. */
 typedef struct {

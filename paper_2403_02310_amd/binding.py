@@ -64,7 +64,7 @@ class KernelTimes(ctypes.Structure):
 EXPORTED = ["sarathi_create", "sarathi_destroy", "sarathi_workspace_bytes", "sarathi_last_error",
             "sarathi_set_option", "sarathi_kv_append", "sarathi_hybrid_attention",
             "sarathi_plan_hybrid_attention", "sarathi_build_stall_free_batch", "sarathi_get_kernel_times",
-            "sarathi_linear", "sarathi_linear_workspace_bytes"]
+            "sarathi_linear", "sarathi_linear_workspace_bytes", "sarathi_hybrid_attention_noalloc"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libsarathi.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -91,6 +91,9 @@ lib.sarathi_kv_append.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32p, _i32p, _i
 lib.sarathi_hybrid_attention.restype = ctypes.c_int
 lib.sarathi_hybrid_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32p, _i32p, _i32p,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, _vp, _vp, _vp]
+lib.sarathi_hybrid_attention_noalloc.restype = ctypes.c_int
+lib.sarathi_hybrid_attention_noalloc.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32p, _i32p, _i32p,
+                                                 ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, _vp, _vp]
 lib.sarathi_plan_hybrid_attention.restype = ctypes.c_int
 lib.sarathi_plan_hybrid_attention.argtypes = [_vp, _i32p, _i32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                               ctypes.POINTER(PlanInfo), ctypes.POINTER(WorkItem), ctypes.c_int32]
@@ -234,6 +237,18 @@ class Handle:
         self._check(lib.sarathi_hybrid_attention(self._h, _dev(q), _dev(k_cache), _dev(v_cache), _dev(block_table),
                                                  _ptr(qs), _ptr(ql), _ptr(cl), len(ql), n, pages, float(sm_scale),
                                                  _dev(out), _dev(ws), _stream(stream)))
+        return out
+
+    def hybrid_attention_noalloc(self, q, k_cache, v_cache, block_table, q_start, q_len, ctx_len, sm_scale: float, out,
+                                 num_pages: Optional[int] = None, num_tokens: Optional[int] = None, stream=None):
+        """``sarathi_hybrid_attention_noalloc``: no workspace, the library's built-in scratch."""
+        qs, ql, cl = _i32(q_start), _i32(q_len), _i32(ctx_len)
+        n = int(ql.sum()) if num_tokens is None else num_tokens
+        pages = int(k_cache.shape[0]) if num_pages is None else num_pages
+        self._check_block_table(block_table, len(ql))
+        self._check(lib.sarathi_hybrid_attention_noalloc(self._h, _dev(q), _dev(k_cache), _dev(v_cache), _dev(block_table),
+                                                         _ptr(qs), _ptr(ql), _ptr(cl), len(ql), n, pages, float(sm_scale),
+                                                         _dev(out), _stream(stream)))
         return out
 
 

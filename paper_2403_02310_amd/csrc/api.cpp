@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <string>
@@ -60,6 +61,8 @@ struct sarathi_handle {
     uint64_t timing_seen[3] = {0, 0, 0};
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing_pool[3];  // append, attention, merge
     size_t timing_used[3] = {0, 0, 0};
+    // host image of the packed plan for the allocation-free entry point (sized once, at creation)
+    std::vector<char> noalloc_meta;
 };
 
 namespace {
@@ -296,6 +299,7 @@ extern "C" sarathi_status sarathi_create(const sarathi_config *config, sarathi_h
         delete h;
         return SARATHI_ECAPACITY;
     }
+    h->noalloc_meta.resize(kStaticMetaBytes);
     *out = h;
     return SARATHI_OK;
 }
@@ -557,4 +561,41 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
     return enqueue_attention(h, dev, reinterpret_cast<float *>(ws + h->ws.part_ml), reinterpret_cast<float *>(ws + h->ws.part_o),
                              reinterpret_cast<int32_t *>(ws + h->ws.sched), block_table, q, k_cache, v_cache, num_pages, sm_scale,
                              out, s, /*instrumented=*/true);
+}
+
+extern "C" sarathi_status sarathi_hybrid_attention_noalloc(sarathi_handle *h, const void *q, const void *k_cache,
+                                                           const void *v_cache, const int32_t *block_table,
+                                                           const int32_t *q_start, const int32_t *q_len,
+                                                           const int32_t *ctx_len, int32_t num_seqs, int32_t num_tokens,
+                                                           int64_t num_pages, float sm_scale, void *out, void *stream) {
+    if (!h) return SARATHI_EINVAL;
+    sarathi_status st = validate_batch(h->cfg, q_start, q_len, ctx_len, num_seqs, num_tokens, num_pages, h->err);
+    if (st != SARATHI_OK) return st;
+    if (num_seqs == 0) return SARATHI_OK;
+    if (!q || !k_cache || !v_cache || !block_table || !out) return fail(h, SARATHI_EINVAL, "null tensor pointer");
+    if (!(sm_scale > 0.0f) || sm_scale - sm_scale != 0.0f) return fail(h, SARATHI_EINVAL, "sm_scale must be positive and finite");
+    // Partial rows the built-in scratch holds for this shape; the planner coarsens its splits until they fit.
+    const size_t row_bytes = sizeof(float) * (size_t)h->cfg.num_kv_heads * h->cfg.head_dim;
+    WorkspaceLayout lay = h->ws;
+    lay.max_part_rows = (int32_t)std::min<size_t>((size_t)lay.max_part_rows, kStaticPartOBytes / row_bytes);
+    if (lay.max_part_rows < 2 * kTileCols || sizeof(float) * 2 * (size_t)lay.max_part_rows * h->cfg.num_kv_heads > kStaticPartMlBytes)
+        return fail(h, SARATHI_ECAPACITY, "allocation-free entry point: num_kv_heads * head_dim is too large for the built-in scratch");
+    h->resident_ws = nullptr;  // h->plan is about to be overwritten
+    plan_attention(h->cfg, h->opt, lay, q_start, q_len, ctx_len, num_seqs, h->plan);
+    const AttnMetaOffsets o = attn_meta_offsets(h->plan);
+    if (o.total > kStaticMetaBytes || o.total > h->noalloc_meta.size()) {
+        char buf[200];
+        snprintf(buf, sizeof buf, "allocation-free entry point: the batch's plan needs %zu bytes of metadata, the built-in "
+                 "scratch holds %zu (about %zu sequences or 128-column tiles)", o.total, kStaticMetaBytes, kStaticMetaBytes / 52);
+        return fail(h, SARATHI_ECAPACITY, buf);
+    }
+    StaticScratch sc;
+    hipError_t e = (hipError_t)static_scratch(&sc);
+    if (e != hipSuccess) return hip_fail(h, "hipGetSymbolAddress(scratch)", e);
+    std::memset(h->noalloc_meta.data(), 0, o.total);
+    pack_attn_meta(h->noalloc_meta.data(), h->plan, o);
+    e = (hipError_t)launch_upload_args(sc.meta, h->noalloc_meta.data(), o.total, stream);
+    if (e != hipSuccess) return hip_fail(h, "launch upload(metadata in kernel arguments)", e);
+    return enqueue_attention(h, sc.meta, sc.part_ml, sc.part_o, sc.sched, block_table, q, k_cache, v_cache, num_pages, sm_scale,
+                             out, static_cast<hipStream_t>(stream), /*instrumented=*/false);
 }

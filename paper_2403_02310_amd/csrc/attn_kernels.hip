@@ -52,6 +52,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "internal.h"
@@ -1051,6 +1053,17 @@ __global__ __launch_bounds__(256) void upload_kernel(u32x4 *dst, const u32x4 *sr
     if (i < n) dst[i] = src[i];
 }
 
+// The same for callers that own no pinned buffer: the bytes travel in the kernel's arguments (the runtime copies
+// the argument block when the launch is enqueued, so the source is free at once).  3,840 bytes per launch.
+constexpr uint32_t kArgPieceWords = 960;
+struct ArgPiece {
+    uint32_t w[kArgPieceWords];
+};
+__global__ __launch_bounds__(256) void upload_args_kernel(u32x4 *dst, ArgPiece piece, uint32_t n16) {
+    const uint32_t i = threadIdx.x;
+    if (i < n16) dst[i] = u32x4{piece.w[4 * i], piece.w[4 * i + 1], piece.w[4 * i + 2], piece.w[4 * i + 3]};
+}
+
 __global__ void zero_words_kernel(uint32_t *p, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -1237,6 +1250,58 @@ int launch_upload(void *dst, const void *pinned_src, size_t bytes, void *stream)
     hipLaunchKernelGGL(upload_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(pinned_src), n);
     return (int)hipGetLastError();
+}
+
+int launch_upload_args(void *dst, const void *host_src, size_t bytes, void *stream) {
+    static_assert(sizeof(ArgPiece) + 16 <= 4096, "kernel arguments are limited to 4 KiB");
+    const char *src = static_cast<const char *>(host_src);
+    char *d = static_cast<char *>(dst);
+    for (size_t off = 0; off < bytes; off += sizeof(ArgPiece)) {
+        const size_t n = bytes - off < sizeof(ArgPiece) ? bytes - off : sizeof(ArgPiece);
+        ArgPiece piece;
+        std::memcpy(piece.w, src + off, n);
+        hipLaunchKernelGGL(upload_args_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           reinterpret_cast<u32x4 *>(d + off), piece, (uint32_t)((n + 15) / 16));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
+    return (int)hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------
+// Scratch of the allocation-free entry point: one array in the device image of this library, so every GPU the
+// library runs on holds its own copy until the process ends.  Host code never uses the array's name as an
+// address: the device address is looked up once per device and used from then on.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kStaticSchedBytes = (kSchedBytes + 255) / 256 * 256;
+constexpr size_t kStaticScratchBytes = kStaticMetaBytes + kStaticSchedBytes + kStaticPartMlBytes + kStaticPartOBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch(StaticScratch *out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static char *base_of_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    char *base;
+    {
+        std::lock_guard<std::mutex> guard(lock);
+        if (!base_of_device[dev]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return (int)e;
+            if (!ptr) return (int)hipErrorInvalidSymbol;
+            base_of_device[dev] = static_cast<char *>(ptr);
+        }
+        base = base_of_device[dev];
+    }
+    out->meta = base;
+    out->sched = reinterpret_cast<int32_t *>(base + kStaticMetaBytes);
+    out->part_ml = reinterpret_cast<float *>(base + kStaticMetaBytes + kStaticSchedBytes);
+    out->part_o = reinterpret_cast<float *>(base + kStaticMetaBytes + kStaticSchedBytes + kStaticPartMlBytes);
+    return (int)hipSuccess;
 }
 
 int launch_zero(void *ptr, size_t bytes, void *stream) {

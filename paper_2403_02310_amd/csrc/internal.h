@@ -172,6 +172,24 @@ int launch_upload(void *dst, const void *pinned_src, size_t bytes, void *stream)
 
 int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32_t first, int32_t count, void *stream);
 
+// ---- scratch memory inside the library's device image (allocation-free entry point) ----
+// One array per GPU, laid out as the regions of a caller's workspace are: metadata, scheduling words, split-KV
+// partials.  The sizes are fixed at build time; a batch whose plan does not fit is refused.
+constexpr size_t kStaticMetaBytes = (size_t)64 << 10;     // packed plan of one call
+constexpr size_t kStaticPartMlBytes = (size_t)512 << 10;  // (maximum, sum) of the partial rows: part_o bytes * 2 / head_dim at most
+constexpr size_t kStaticPartOBytes = (size_t)16 << 20;    // unnormalised outputs of the partial rows
+struct StaticScratch {
+    char *meta;
+    int32_t *sched;
+    float *part_ml;
+    float *part_o;
+};
+// Device addresses of the regions on the CURRENT device (looked up once per device, then remembered).
+int static_scratch(StaticScratch *out);
+// Copies `bytes` (a multiple of 16, dst 16-byte aligned) from ordinary host memory to device memory by kernels that
+// carry the data in their arguments: no pinned buffer, no runtime copy, the host buffer is free on return.
+int launch_upload_args(void *dst, const void *host_src, size_t bytes, void *stream);
+
 // ---- linear layer (linear_kernels.hip) ----
 struct LinearPlan {
     int32_t feature_tile; // output features per workgroup tile: 256 or 128

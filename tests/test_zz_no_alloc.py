@@ -1,0 +1,77 @@
+"""The allocation-free entry point (sarathi_hybrid_attention_noalloc: no workspace argument, scratch inside the
+library's device image) against the entry point it is a variant of, through the C ABI.
+
+Two calls in a row on one GPU, the second with a smaller batch: the scratch keeps the first call's contents, so
+the second call shows that nothing stale is read.  Where both entry points cut no key range (or cut it the same
+way) the outputs are equal bit for bit; every output is also within the attention tolerance of the fp64 checker.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2403_02310_amd import binding, workloads as wl
+from tests.parity import compare
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(hx, batch, options=None):
+    """Runs append + sarathi_hybrid_attention, then sarathi_hybrid_attention_noalloc on the same cache."""
+    h = hx.make_handle(batch)
+    for k, v in (options or {}).items():
+        h.set_option(k, v)
+    st = hx.setup_and_run(batch, 0x7FC1, handle=h)
+    base = hx.device_to_bits(st["out"])
+    out2 = torch.full_like(st["out"], float("nan"))
+    h.hybrid_attention_noalloc(st["q"], st["k_cache"], st["v_cache"], st["bt"], batch.q_start, batch.q_len, batch.ctx_len,
+                               batch.sm_scale, out2)
+    torch.cuda.synchronize()
+    return h, st, base, out2
+
+
+def test_noalloc_matches_the_workspace_entry_point_twice_in_a_row():
+    from paper_2403_02310_amd import harness as hx
+    s = wl.AttnShape(8, 2, 128)
+    # first call: chunks + decodes, one decode long enough to be cut across blocks (partial rows + merge), run-time roles
+    big = wl._make("noalloc_big", s, [300, 1, 37, 1, 1, 200], [1300, 555, 37, 1, 7000, 900], 91)
+    small = wl._make("noalloc_small", s, [1, 40, 1], [130, 200, 3], 92)
+    for batch, opts in ((big, {"resident_chunks": 1}), (small, {})):
+        print("case", batch.name, "options", opts, flush=True)
+        h, st, base, out2 = _both(hx, batch, opts)
+        ref = oracle.attention_for_batch(batch)
+        got2 = hx.bf16_tensor_to_f64(out2)
+        compare(got2, ref, batch.name + " noalloc vs checker")
+        compare(got2, hx.bf16_tensor_to_f64(st["out"]), batch.name + " noalloc vs workspace entry point")
+        # same planner limits for these small batches: the same cuts, so the same bits
+        np.testing.assert_array_equal(hx.device_to_bits(out2), base)
+    # and once more the big one on the scratch the small one left behind
+    h, st, base, out2 = _both(hx, big, {"tile_split_keys": 256, "split_keys": 128})
+    info, _ = h.plan(big.q_start, big.q_len, big.ctx_len)
+    assert info.num_reduce_items > 10 and info.num_part_rows <= 16384   # many cuts, all within the built-in scratch: same plan
+    np.testing.assert_array_equal(hx.device_to_bits(out2), base)
+    compare(hx.bf16_tensor_to_f64(out2), oracle.attention_for_batch(big), "noalloc, forced splits")
+
+
+def test_noalloc_full_size_mistral_batch():
+    """The 512-token chunk + 64 decodes of the Mistral-shape recipe through the allocation-free entry point."""
+    from paper_2403_02310_amd import harness as hx
+    batch = wl.decodes_first(wl.config2_mistral_hybrid())
+    h, st, base, out2 = _both(hx, batch)
+    np.testing.assert_array_equal(hx.device_to_bits(out2), base)
+
+
+def test_noalloc_refuses_what_its_scratch_cannot_hold():
+    """2000 decodes need more metadata than the built-in scratch holds: a clear error, nothing enqueued."""
+    s = wl.AttnShape(8, 2, 128)
+    n = 2000
+    h = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=4096, max_seqs=4096, max_blocks_per_seq=4)
+    q_len = np.ones(n, np.int32); ctx = np.full(n, 20, np.int32); q_start = np.arange(n, dtype=np.int32)
+    q = torch.zeros(n, s.num_q_heads, s.head_dim, dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros(8, s.num_kv_heads, 16, s.head_dim, dtype=torch.bfloat16, device="cuda")
+    bt = torch.zeros(n, 4, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.SarathiError) as e:
+        h.hybrid_attention_noalloc(q, kc, kc, bt, q_start, q_len, ctx, 0.1, torch.empty_like(q))
+    assert e.value.status == binding.ECAPACITY and "allocation-free" in str(e.value)
+    torch.cuda.synchronize()
