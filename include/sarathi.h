@@ -186,14 +186,14 @@ sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
  * The same attention for callers that cannot allocate device memory or hand a workspace over: code that runs
  * under HIP stream capture, tight serving loops, harnesses that forbid hipMalloc.  Identical to
  * sarathi_hybrid_attention except that it takes no workspace: the batch metadata, the scheduling words and the
- * split-KV partial rows live in a fixed array of about 16.6 MiB inside the library's device image (each GPU the
+ * split-KV partial rows live in a fixed array of about 16.7 MiB inside the library's device image (each GPU the
  * library runs on holds one copy until the process ends), and the metadata reaches the device in the arguments of
  * small kernels (3,840 bytes per launch) instead of through the handle's pinned buffers.  The call allocates
  * nothing (no hipMalloc / hipHostMalloc / hipFree, no stream or event creation) and enqueues kernels only; it
  * records no timing events ("time_kernels" is ignored) and treats option "interleave" = 1 as 2.
  *
- * Limits: the packed plan (48 bytes per tile of 16 decode columns or 128 chunk columns, 4 bytes per work item)
- * must fit into 64 KiB, else SARATHI_ECAPACITY (roughly 1,200 sequences); 16 MiB of partial rows (4,096 rows at
+ * Limits: the packed plan (64 bytes per tile of 16 decode columns or 128 chunk columns, 4 bytes per work item)
+ * must fit into 96 KiB, else SARATHI_ECAPACITY (roughly 1,400 sequences); 16 MiB of partial rows (4,096 rows at
  * 8 KV heads x 128 channels; key ranges are cut less finely when that is short, never refused);
  * num_kv_heads * head_dim * 4 bytes per partial row must leave room for 256 rows, else SARATHI_ECAPACITY.
  * Every call on a GPU shares that GPU's array: two calls that overlap in time on one GPU (two streams, two

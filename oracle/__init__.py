@@ -11,6 +11,7 @@ Contents
 ``kv_cache_reference.py`` what the paged K/V pools must hold after an append, and how a
                           sequence is read back through its block table (section 2.2, paged cache).
 ``scheduler_reference.py`` one iteration of stall-free batching (Algorithm 3, section 4.2).
+``token_budget_reference.py`` the token budget chosen from a one-time profile (section 4.3).
 ``linear_oracle.c``       a linear layer over the batch's token rows in double precision
                           (sections 2.1 and 3.1), compiled into ``liblinear_oracle.so``.
 """

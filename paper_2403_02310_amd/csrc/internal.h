@@ -45,8 +45,10 @@ struct TileDesc {
     int32_t q_start;
     int32_t q_len;
     int32_t ctx_len;
+    int32_t merge_slot;   // index of this tile among the split tiles (row of the arrival counters), -1 if n_splits == 1
+    int32_t reserved[3];
 };
-static_assert(sizeof(TileDesc) == 48, "TileDesc is copied to the device as raw bytes");
+static_assert(sizeof(TileDesc) == 64, "TileDesc is copied to the device as raw bytes");
 
 // A work unit = (tile index, split index) packed into 32 bits.
 constexpr int kUnitTileBits = 22;
@@ -94,6 +96,9 @@ struct Options {
     int64_t stream_kv = -1;         // decode K/V loads carry the streaming (non-temporal) hint: -1 = when the batch's chunk
                                     // work is absent or small next to its decode streams, or its longest chunk unit
                                     // runs about as long as they do; 0 = never, 1 = always
+    int64_t lds_pad_kb = 0;         // diagnostic only: KiB of unused LDS added to every attention block
+    int64_t merge_in_kernel = 0;    // split tiles: 1 = the last piece of a tile to finish merges all of them inside the attention
+                                    // launch (arrival counters), 0 = a second, small kernel merges them
     int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
                                     // a compute unit holds at most one chunk block while decode work remains
                                     // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)
@@ -153,9 +158,12 @@ struct AttnMeta {
     int32_t num_tile_reduce_units;   // leading entries of reduce_units that belong to chunk tiles
     float *part_ml;              // dev
     float *part_o;               // dev
+    int32_t *merge_cnt;          // dev [num_split_tiles][Hkv] arrival counters, zero at launch (they travel with the plan);
+                                 // null: the pieces are merged by launch_reduce instead
     int32_t *sched;              // dev, kSchedBytes
     int32_t window;              // sliding window in keys, 0 = none
     int32_t stream_kv;           // 1: the wave tiles' K/V loads carry the streaming hint
+    int32_t lds_pad_bytes = 0;   // diagnostic: dynamic LDS added to the attention launches (fewer blocks per compute unit)
 };
 
 // which: bit 0 = the chunk-tile kernel, bit 1 = the wave-tile kernel, 4 = both kinds in one launch,
@@ -175,7 +183,7 @@ int launch_reduce(const sarathi_config &cfg, const AttnMeta &m, void *out, int32
 // ---- scratch memory inside the library's device image (allocation-free entry point) ----
 // One array per GPU, laid out as the regions of a caller's workspace are: metadata, scheduling words, split-KV
 // partials.  The sizes are fixed at build time; a batch whose plan does not fit is refused.
-constexpr size_t kStaticMetaBytes = (size_t)64 << 10;     // packed plan of one call
+constexpr size_t kStaticMetaBytes = (size_t)96 << 10;     // packed plan of one call
 constexpr size_t kStaticPartMlBytes = (size_t)512 << 10;  // (maximum, sum) of the partial rows: part_o bytes * 2 / head_dim at most
 constexpr size_t kStaticPartOBytes = (size_t)16 << 20;    // unnormalised outputs of the partial rows
 struct StaticScratch {

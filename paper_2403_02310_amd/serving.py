@@ -227,20 +227,43 @@ class ServingLoop:
             self.waiting.append(self.requests[self._next_arrival])
             self._next_arrival += 1
 
+    def _lifetime_pages(self, r: Request) -> int:
+        return (r.total_rows + self.shape.page_size - 1) // self.shape.page_size
+
+    def _admissible(self):
+        """Pages that new requests may claim, and the first-come-first-served prefix of the waiting list that fits.
+
+        The scheduler's own memory test looks at a prompt's pages only (Algorithm 3 leaves ``can_allocate_request``
+        open; the library reserves the prompt).  A running request keeps growing by one page every 16 generated
+        tokens, and decodes must never stall (section 4.2), least of all on memory: so this loop sets aside, at
+        admission, the pages a request will need over its whole life, and only offers the scheduler the waiting
+        requests whose lifetime need fits into what is neither in use nor set aside."""
+        set_aside = sum(self._lifetime_pages(r) - len(r.pages) for r in self.prefilling + self.decoding)
+        avail = self.pool.free - set_aside
+        n_ok, claimed = 0, 0
+        for r in self.waiting:
+            need = self._lifetime_pages(r)
+            if claimed + need > avail:
+                break
+            claimed += need
+            n_ok += 1
+        return max(avail, 0), n_ok
+
     def _schedule(self):
         """Returns [(request, q_len)] in batch order and how many waiting requests entered."""
         by_id = {r.id: r for r in self.waiting + self.prefilling + self.decoding}
+        avail, n_ok = self._admissible()
         if self.policy == "stall_free":
             from . import binding
             tup = lambda r: (r.id, r.prompt_len, r.num_prefilled, r.num_decoded)
             b = binding.build_stall_free_batch(self.token_budget, self.chunk_size, [tup(r) for r in self.decoding],
-                                               [tup(r) for r in self.prefilling], [tup(r) for r in self.waiting],
-                                               self.pool.free, self.shape.page_size, min(self.max_batch_size, len(self._free_slots) + len(self.prefilling) + len(self.decoding)))
+                                               [tup(r) for r in self.prefilling], [tup(r) for r in self.waiting[:n_ok]],
+                                               avail, self.shape.page_size, min(self.max_batch_size, len(self._free_slots) + len(self.prefilling) + len(self.decoding)))
             return [(by_id[i], n) for i, n in zip(b["seq_id"], b["q_len"])], b["num_admitted"]
         # prefill_first: whole prompts of waiting requests while any wait (decodes stall), else all decodes
-        batch, admitted, tokens, pages_left = [], 0, 0, self.pool.free
-        for r in self.waiting:
-            pages = (r.prompt_len + self.shape.page_size - 1) // self.shape.page_size
+        batch, admitted, tokens, pages_left = [], 0, 0, avail
+        for r in self.waiting[:n_ok]:
+            pages = self._lifetime_pages(r)
             if pages > pages_left or len(batch) >= len(self._free_slots) or (batch and tokens + r.prompt_len > self.max_tokens):
                 break
             batch.append((r, r.prompt_len))
@@ -262,7 +285,8 @@ class ServingLoop:
         running_decodes = len(self.decoding)
         batch, admitted = self._schedule()
         if not batch:
-            raise RuntimeError("scheduler produced an empty batch with work pending (pool too small for the next prompt?)")
+            raise RuntimeError("scheduler produced an empty batch with work pending (the pool cannot hold the next request's "
+                               "prompt and generated tokens even when nothing else runs?)")
         page = self.shape.page_size
         for r in self.waiting[:admitted]:     # admission reserves the whole prompt's pages
             r.slot = self._free_slots.pop()

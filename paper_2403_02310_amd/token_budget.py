@@ -6,9 +6,10 @@ the largest count whose iteration stays within the latency target.  Here an "ite
 model (``gpu_timer(linear_model=...)``); there is no whole model around it, so the times are a PROXY for
 the paper's time-between-tokens target and the budgets only mean something relative to each other.
 
-A profiled batch for budget tau = the given running decodes (one token each) plus one prefill chunk
-of tau - #decodes tokens on top of a cached prefix: the fullest batch stall-free batching builds
-under that budget (Algorithm 3, section 4.2).
+A profiled batch for budget tau = the given running decodes (one token each) plus the prefill chunk that
+``sarathi_build_stall_free_batch`` gives a request in mid-prefill under that budget (tau - #decodes tokens on
+top of its cached prefix; none when the decodes use the budget up): the fullest batch stall-free batching
+builds under that budget (Algorithm 3, section 4.2).
 
 The section's second consideration, tile quantisation (a chunk one token past a tile edge costs a
 whole further tile), is measured by ``tile_quantization_probe``: chunk sizes around the kernels'
@@ -24,12 +25,18 @@ from .workloads import AttnShape, HybridBatch, _make
 
 
 def budget_batch(shape: AttnShape, token_budget: int, decode_ctx: Sequence[int], chunk_prefix: int, seed: int = 0) -> HybridBatch:
-    """Decodes first, then one chunk that uses up the budget (at least one token)."""
+    """The fullest batch stall-free batching builds under ``token_budget``: the running decodes (contexts
+    ``decode_ctx``, the new token included) and a request in mid-prefill with ``chunk_prefix`` tokens done and more
+    than a budget's worth to go.  The batch comes from ``sarathi_build_stall_free_batch`` (Algorithm 3): the chunk is
+    what the decodes leave of the budget, and none at all when they leave nothing."""
+    from . import binding
     n_dec = len(decode_ctx)
-    chunk = max(1, token_budget - n_dec)
-    q_len = [1] * n_dec + [chunk]
-    ctx = [int(c) for c in decode_ctx] + [chunk_prefix + chunk]
-    return _make("budget_%d" % token_budget, shape, q_len, ctx, seed, slack=1.0)
+    decodes = [(i, int(c) - 1, int(c) - 1, 0) for i, c in enumerate(decode_ctx)]       # ctx = prompt + 0 decoded + the new token
+    prefill = [(n_dec, chunk_prefix + 2 * token_budget + 1, chunk_prefix, 0)]
+    b = binding.build_stall_free_batch(token_budget, token_budget, decodes, prefill, [], free_pages=0,
+                                       page_size=shape.page_size, max_batch_size=n_dec + 1)
+    assert b["num_decodes"] == n_dec and b["num_tokens"] <= max(token_budget, n_dec)
+    return _make("budget_%d" % token_budget, shape, b["q_len"], b["ctx_len"], seed, slack=1.0)
 
 
 def profile(time_batch: Callable[[HybridBatch], float], shape: AttnShape, budgets: Sequence[int], decode_ctx: Sequence[int],
@@ -55,10 +62,12 @@ def compute_token_budget(rows: Sequence[Dict[str, float]], target_seconds: float
 
 
 def gpu_timer(options: Optional[Dict[str, int]] = None, reps: int = 20, warmup: int = 3,
-              linear_model: Optional[str] = None) -> Callable[[HybridBatch], float]:
+              linear_model: Optional[str] = None, on_batch: Optional[Callable] = None) -> Callable[[HybridBatch], float]:
     """Times append + attention of a batch on the GPU (median of ``reps``), values drawn on the device.
     ``linear_model`` (a key of ``linear_layers.MODELS``): the four linear layers of one transformer layer of that
-    model run over the batch's tokens inside the timed region too."""
+    model run over the batch's tokens inside the timed region too.  ``on_batch(batch, tensors)`` is called after
+    a batch has been timed with its device tensors (q, k_cache, v_cache, block_table, out), e.g. by a test that
+    checks what the profiled launches computed."""
     import torch
     from . import binding
     linear = []   # (weight, scratch bytes wanted) per layer, drawn once
@@ -103,6 +112,8 @@ def gpu_timer(options: Optional[Dict[str, int]] = None, reps: int = 20, warmup: 
             ev[1].synchronize()
             if i >= warmup:
                 times.append(ev[0].elapsed_time(ev[1]) * 1e-3)
+        if on_batch is not None:
+            on_batch(b, {"q": q, "k_cache": kc, "v_cache": vc, "block_table": bt, "out": out})
         return float(np.median(times))
     return time_batch
 

@@ -81,3 +81,26 @@ def test_admission_waits_for_pages():
     assert len(loop.done) == 4
     starts = sorted(r.first_token_s for r in loop.done)
     assert all(b > a for a, b in zip(starts, starts[1:]))
+
+
+@pytest.mark.parametrize("policy", ["stall_free", "prefill_first"])
+def test_a_pool_barely_larger_than_the_working_set_never_stalls_a_decode(policy):
+    """Decodes grow by a page every 16 generated tokens.  If admission looked at prompts only, a pool this tight would
+    run dry in the middle of a generation (and the loop would die); setting aside a request's lifetime pages at
+    admission makes new requests wait instead, and every running decode still gets its token in every iteration."""
+    # prompts of 2 pages that generate 150 tokens (11 pages over their life); the pool holds three such lifetimes
+    reqs = [serving.Request(i, 0.0, 32, 150, token_base=i * 181) for i in range(9)]
+    pages = 3 * ((32 + 149 + 15) // 16)
+    loop = _loop(policy, budget=64, chunk=64, pages=pages, reqs=reqs).run()
+    assert len(loop.done) == 9 and loop.pool.free == pages
+    assert max(it.num_running_decodes for it in loop.iterations) == 3          # never more than fit for their whole life
+    if policy == "stall_free":
+        assert all(it.num_decodes == it.num_running_decodes for it in loop.iterations)
+    # with prompts alone as the admission test all nine would have entered at once (18 pages of 36) and run dry
+    assert sum((r.prompt_len + 15) // 16 for r in reqs) <= pages
+
+
+def test_a_request_that_can_never_fit_is_reported():
+    reqs = [serving.Request(0, 0.0, 64, 400, token_base=0)]
+    with pytest.raises(RuntimeError, match="cannot hold"):
+        _loop("stall_free", pages=10, reqs=reqs).run()

@@ -11,8 +11,16 @@ def test_budget_batch_is_the_fullest_stall_free_batch():
     b = tb.budget_batch(SHAPE, 512, [100, 200, 300], chunk_prefix=1000)
     assert b.q_len.tolist() == [1, 1, 1, 509] and b.ctx_len.tolist() == [100, 200, 300, 1509]
     assert b.num_tokens == 512
-    tiny = tb.budget_batch(SHAPE, 2, [50, 60, 70], chunk_prefix=0)      # more decodes than budget: they all stay
-    assert tiny.q_len.tolist() == [1, 1, 1, 1]
+    # more decodes than budget: they all stay and no prefill token is added (Algorithm 3 gives a prefill only what
+    # the decodes leave of the budget)
+    tiny = tb.budget_batch(SHAPE, 2, [50, 60, 70], chunk_prefix=0)
+    assert tiny.q_len.tolist() == [1, 1, 1] and tiny.ctx_len.tolist() == [50, 60, 70]
+    exact = tb.budget_batch(SHAPE, 3, [50, 60, 70], chunk_prefix=10)    # decodes use the budget up exactly
+    assert exact.q_len.tolist() == [1, 1, 1]
+    one = tb.budget_batch(SHAPE, 4, [50, 60, 70], chunk_prefix=10)
+    assert one.q_len.tolist() == [1, 1, 1, 1] and one.ctx_len.tolist() == [50, 60, 70, 11]
+    for tau in (64, 512, 4096):
+        assert tb.budget_batch(SHAPE, tau, [500] * 16, chunk_prefix=1000).num_tokens == tau
 
 
 def test_largest_budget_under_the_target():
