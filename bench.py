@@ -25,8 +25,22 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the attention kernels (fetch + write), from two `rocprofv3 --pmc` runs
 # (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read on a plain copy of known size;
-# the runs and the scaling are recorded in profiles/ (attention_c2_mistral_hybrid.md and its siblings).
-MEASURED_TRAFFIC_BYTES = {"c2": 606.4e6, "c3": 1480.8e6, "c4": 5015.9e6, "c4_chunks": 344.4e6}
+# the runs and the scaling are recorded in the named files under profiles/.  The figures belong to the
+# recipe's own seed and the library's default options: a run with another seed, other options or other
+# values reports no traffic (null) rather than somebody else's.
+MEASURED_TRAFFIC_BYTES = {"c2": (606.4e6, "profiles/attention_c2_mistral_hybrid.md"),
+                          "c3": (1480.8e6, "profiles/attn_wave_kernel_c3_decode_only.md"),
+                          "c4": (5015.9e6, "profiles/attention_c4_yi_long.md"),
+                          "c4_chunks": (344.4e6, "profiles/attn_chunk_kernel_c4_chunks.md")}
+
+
+def measured_traffic(args):
+    """(bytes, source) of the profiled launch this run repeats, or (None, reason)."""
+    if args.seed is not None or args.opt or args.values != "normal":
+        return None, "not measured for this seed / these options / these values"
+    if args.workload not in MEASURED_TRAFFIC_BYTES:
+        return None, "no counter run recorded for this workload"
+    return MEASURED_TRAFFIC_BYTES[args.workload]
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
@@ -82,7 +96,10 @@ def run_sweep(args, binding, harness, torch) -> int:
     flops = 4.0 * s.head_dim * s.num_q_heads * (prompt * (prompt + 1) / 2)
     reps = max(3, min(args.steps, 10))
     curve = {}
-    for c in (8192, 2048, 1024, 512, 256, 128, 64):
+    sizes = [int(x) for x in args.sweep_chunks.split(",")] if args.sweep_chunks else [8192, 2048, 1024, 512, 256, 128, 64]
+    for c in sizes:
+        if c < 1 or prompt % c:
+            raise SystemExit("bench.py: --sweep-chunks takes divisors of %d" % prompt)
         n_it = prompt // c
         qs, ql, cl = i32(0), i32(c), [i32((i + 1) * c) for i in range(n_it)]
 
@@ -108,12 +125,13 @@ def run_sweep(args, binding, harness, torch) -> int:
         torch.cuda.synchronize()
         us = (time.perf_counter() - t0) * 1e6 / reps
         curve[str(c)] = {"iterations": n_it, "total_us": us, "mfma_frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
-    one_shot = curve["8192"]["total_us"]
-    for v in curve.values():
-        v["overhead_vs_one_shot"] = v["total_us"] / one_shot
-    best = curve["2048"]
+    if "8192" in curve:
+        one_shot = curve["8192"]["total_us"]
+        for v in curve.values():
+            v["overhead_vs_one_shot"] = v["total_us"] / one_shot
+    best = curve.get("2048") or curve[str(sizes[0])]
     print(json.dumps({
-        "metric": "chunked prefill of one 8192-token prompt (KV append + attention per chunk): prompt tokens/s at chunk 2048",
+        "metric": "chunked prefill of one 8192-token prompt (KV append + attention per chunk): prompt tokens/s at chunk %s" % ("2048" if "2048" in curve else sizes[0]),
         "value": prompt / (best["total_us"] * 1e-6), "unit": "tokens/s", "n_gpus": 1, "steps": reps, "warmup": 1,
         "ms_per_step": best["total_us"] * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -266,6 +284,7 @@ def main() -> int:
                     help="normal: the workloads' N(0,1) values (every reported figure); zeros: all-zero Q/K/V or x/w, a "
                          "diagnostic that shows how far the chip's clock, which falls with the matrix pipes' switching "
                          "power, moves the MFMA-bound kernels (no parity check, no CPU baseline)")
+    ap.add_argument("--sweep-chunks", default="", help="c5_sweep only: comma-separated chunk sizes (default: 8192,2048,...,64)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--opt", action="append", default=[], help="library tuning knob name=value (repeatable)")
@@ -466,15 +485,22 @@ def main() -> int:
         has_chunk, has_wave = info.num_tile_items > 0, info.num_items > info.num_tile_items
         attn_kernel = ("attn_hybrid_kernel (chunk-tile and wave-tile blocks in one launch)" if has_chunk and has_wave
                        else "attn_chunk_kernel" if has_chunk else "attn_wave_kernel")
+        # The rows whose bytes and flops are counted are complete only after the merge of the tiles that were cut
+        # (when there are any): the figure is over the attention launch plus that merge.
+        merge_us = result["kernel_us"]["merge"]
+        kern_us = attn_us + merge_us
+        if merge_us > 0:
+            attn_kernel += " + splitkv_reduce_kernel"
+        traffic, traffic_src = measured_traffic(args)
         if mfma_bound:
-            ach = alg_flops / (attn_us * 1e-6) / 1e12
+            ach = alg_flops / (kern_us * 1e-6) / 1e12
             result["roofline"] = {"bound": "mfma", "kernel": attn_kernel, "achieved": ach,
                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                                  "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
+                                  "traffic": traffic, "traffic_source": traffic_src, "duration_us": kern_us}
         else:
-            ach = alg_bytes / (attn_us * 1e-6) / 1e9
+            ach = alg_bytes / (kern_us * 1e-6) / 1e9
             result["roofline"] = {"bound": "hbm", "kernel": attn_kernel, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                                  "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
+                                  "traffic": traffic, "traffic_source": traffic_src, "duration_us": kern_us}
 
     # ---- CPU baseline: the fp64 checker as it stands, on the host cores, bounded sample ----
     if not args.no_cpu_baseline:

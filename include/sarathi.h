@@ -117,6 +117,14 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * "window" (sliding-window attention as in the paper's Table 1 for Mistral-7B: with window W > 0 the
  * query at position p reads keys p-W+1 .. p only; 0 = every key up to p; pages in front of every
  * window of a sequence are never dereferenced),
+ * "decode_blocks_per_cu" (launches that hold decodes / 16-column tiles only: 1 = one block per compute unit, so
+ * that blocks start longest first as units fall free, which shortens the tail of small batches; 2 = as many as fit;
+ * -1 = automatic: one for up to 1024 blocks),
+ * "merge_in_kernel" (key ranges cut into pieces: 0 = a second small kernel merges the pieces, 1 = the piece that
+ * finishes last merges them inside the attention launch; results are bitwise reproducible either way),
+ * "inline_append" (0/1: sarathi_kv_append sends up to 224 page records in its kernel's arguments instead of
+ * letting the blocks read them from the pinned buffer), "lds_pad_kb" (diagnostic: KiB of unused LDS per
+ * attention block, which lowers the number of blocks a compute unit holds),
  * "time_kernels" (0/1/2, see sarathi_get_kernel_times), "time_every" (n >= 1: only every n-th launch of a
  * kind is bracketed, so that a timed run carries few events; default 1).
  * Unknown names return SARATHI_EINVAL. */

@@ -227,6 +227,18 @@ sarathi_status enqueue_attention(sarathi_handle *h, char *dev, float *part_ml, f
     m.sched = sched;
     m.window = (int32_t)h->opt.window;
     m.lds_pad_bytes = (int32_t)h->opt.lds_pad_kb * 1024;
+    {
+        // A small decode-only batch whose blocks are all resident at once shares the memory system evenly among
+        // them, so the longest decode runs at a 512th of the bandwidth for most of its life and then alone at what
+        // one block can pull (~36 GB/s): a tail of 15-20 us on 64 decodes.  With one block per compute unit the blocks
+        // start longest first as units fall free and each streams at twice the share; one block per unit already
+        // reaches the chip's streaming rate (256 blocks x 25.5 GB/s).  Measured on 48 ... 128 decodes: -12 to -20 %;
+        // from ~192 decodes on the launch is long enough for two per unit to win by 2-4 %.
+        const int64_t wave_blocks = (int64_t)((int32_t)pl.units.size() - pl.num_tile_units) * h->cfg.num_kv_heads;
+        const bool wave_only = pl.num_tile_units == 0;
+        const bool one = h->opt.decode_blocks_per_cu == 1 || (h->opt.decode_blocks_per_cu < 0 && wave_blocks <= 1024);
+        if (wave_only && one && m.lds_pad_bytes == 0) m.lds_pad_bytes = kOneBlockPerUnitLdsPad;
+    }
     // Rough durations: chunk work with one block per compute unit (~0.65 us per 32-key step), and the time
     // the decodes need to stream their keys and values (~5 bytes/ps).
     const double chunk_us = (double)pl.tile_unit_steps * h->cfg.num_kv_heads * 0.65 / kChunkBlocksForRoles;
@@ -368,6 +380,15 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
     if (std::strcmp(name, "stream_kv") == 0) {
         if (value < -1 || value > 1) return fail(h, SARATHI_EINVAL, "stream_kv must be -1, 0 or 1");
         h->opt.stream_kv = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "decode_blocks_per_cu") == 0) {
+        if (value != -1 && value != 1 && value != 2) return fail(h, SARATHI_EINVAL, "decode_blocks_per_cu must be -1, 1 or 2");
+        h->opt.decode_blocks_per_cu = value;
+        return SARATHI_OK;
+    }
+    if (std::strcmp(name, "inline_append") == 0) {
+        h->opt.inline_append = value != 0;
         return SARATHI_OK;
     }
     if (std::strcmp(name, "lds_pad_kb") == 0) {
@@ -527,6 +548,7 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     hipStream_t s = static_cast<hipStream_t>(stream);
     AppendMeta m;
     m.units = static_cast<const AppendUnit *>(h->staging_dev[slot]);
+    if (h->opt.inline_append) m.units_host = units;
     m.block_table = block_table;
     m.max_blocks = h->cfg.max_blocks_per_seq;
     m.num_units = (int32_t)n_units;

@@ -1274,8 +1274,18 @@ struct AppendParams {
     uint32_t copy_blocks;
 };
 
+// Small batches carry their records in the kernel's arguments (the argument block is on the device when the
+// blocks start; a record in pinned host memory is a read across the host link at the head of every block's
+// chain of dependent loads: record -> block-table entry -> stores).
+constexpr int kInlineAppendUnits = 224;
+struct AppendParamsInline {
+    AppendParams base;
+    AppendUnit units[kInlineAppendUnits];
+};
+static_assert(sizeof(AppendParamsInline) <= 4096, "kernel arguments are limited to 4 KiB");
+
 template <int D>
-__global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
+__device__ __forceinline__ void kv_append_block(const AppendParams &p, const AppendUnit *units) {
     constexpr int kPieces = D / 8;  // 16-byte pieces of one K row
     if (blockIdx.x < p.copy_blocks) {
         const uint32_t i = blockIdx.x * D + threadIdx.x;
@@ -1285,7 +1295,7 @@ __global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
     const unsigned blk = blockIdx.x - p.copy_blocks;
     const int unit = (int)(blk / (unsigned)p.num_kv_heads);
     const int h = (int)(blk % (unsigned)p.num_kv_heads);
-    const u32x4 rec = *reinterpret_cast<const u32x4 *>(p.units + unit);
+    const u32x4 rec = *reinterpret_cast<const u32x4 *>(units + unit);
     const int lo = (int)(rec[3] & 0xFFu), hi = (int)(rec[3] >> 8);
     const int n = hi - lo;
     const int64_t row_stride = (int64_t)p.num_kv_heads * D;
@@ -1340,6 +1350,15 @@ __global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
     }
 }
 
+template <int D>
+__global__ __launch_bounds__(D) void kv_append_kernel(AppendParams p) {
+    kv_append_block<D>(p, p.units);
+}
+template <int D>
+__global__ __launch_bounds__(D) void kv_append_inline_kernel(AppendParamsInline p) {
+    kv_append_block<D>(p.base, p.units);
+}
+
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
@@ -1362,6 +1381,16 @@ int launch_kv_append(const sarathi_config &cfg, const AppendMeta &m, const void 
     p.copy_blocks = (p.copy_n16 + (uint32_t)cfg.head_dim - 1) / (uint32_t)cfg.head_dim;
     const unsigned blocks = p.copy_blocks + (unsigned)m.num_units * (unsigned)cfg.num_kv_heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (m.units_host && m.num_units <= kInlineAppendUnits) {
+        AppendParamsInline pi;
+        pi.base = p;
+        std::memcpy(pi.units, m.units_host, sizeof(AppendUnit) * (size_t)m.num_units);
+        if (cfg.head_dim == 128)
+            hipLaunchKernelGGL(kv_append_inline_kernel<128>, dim3(blocks), dim3(128), 0, st, pi);
+        else
+            hipLaunchKernelGGL(kv_append_inline_kernel<64>, dim3(blocks), dim3(64), 0, st, pi);
+        return (int)hipGetLastError();
+    }
     if (cfg.head_dim == 128)
         hipLaunchKernelGGL(kv_append_kernel<128>, dim3(blocks), dim3(128), 0, st, p);
     else

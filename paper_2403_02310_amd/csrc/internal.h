@@ -25,6 +25,8 @@ constexpr int kSchedCuSlots = 4096;
 constexpr int kSchedMaxKvHeads = 128;
 constexpr size_t kSchedBytes = sizeof(int32_t) * (kSchedCuSlots + 2 * kSchedMaxKvHeads);
 constexpr int kChunkBlocksForRoles = 256;   // one per compute unit
+// Dynamic LDS that, added to a wave-tile block's own 17-34 KiB, leaves room for one such block per compute unit (160 KiB).
+constexpr int kOneBlockPerUnitLdsPad = 64 * 1024;
 
 // One tile of query columns of one sequence.  A "column" is one (query row, query head inside
 // a KV group) pair: col = row*G + head_in_group.  Its key range key_lo..n_keys-1 (key_lo = 0
@@ -96,6 +98,10 @@ struct Options {
     int64_t stream_kv = -1;         // decode K/V loads carry the streaming (non-temporal) hint: -1 = when the batch's chunk
                                     // work is absent or small next to its decode streams, or its longest chunk unit
                                     // runs about as long as they do; 0 = never, 1 = always
+    int64_t decode_blocks_per_cu = -1;  // launches of wave tiles only: 2 = as many blocks per compute unit as fit, 1 = one (unused LDS
+                                    // keeps a second one out, so blocks start longest first as units fall free instead of
+                                    // all at once); -1 = one for up to 1024 blocks, two beyond
+    int64_t inline_append = 1;      // KV append: up to 224 page records travel in the kernel's arguments (else all are read from the pinned buffer)
     int64_t lds_pad_kb = 0;         // diagnostic only: KiB of unused LDS added to every attention block
     int64_t merge_in_kernel = 0;    // split tiles: 1 = the last piece of a tile to finish merges all of them inside the attention
                                     // launch (arrival counters), 0 = a second, small kernel merges them
@@ -133,6 +139,8 @@ inline int64_t max_append_units(const sarathi_config &cfg) {
 
 struct AppendMeta {
     const AppendUnit *units;     // [num_units]; device memory, or pinned host memory by the address the device uses for it
+    const AppendUnit *units_host = nullptr;  // the same records as the host addresses them (null: not host-readable);
+                                             // few enough of them travel in the kernel's arguments instead
     const int32_t *block_table;  // dev [S][max_blocks]
     int32_t max_blocks;
     int32_t num_units;
