@@ -228,6 +228,40 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
         const int64_t balanced = ceil_div(std::max<int64_t>(tile_floor, share * 42 / 100), kTileKeys) * kTileKeys;
         tile_split = std::min(tile_split, balanced);
     }
+    if (opt.tile_split_keys <= 0 && !has_wave_tiles && n_chunk_tiles > 0 && (int64_t)n_chunk_tiles * cfg.num_kv_heads < 512) {
+        // A chunk-only batch with fewer tiles than block slots (two per compute unit), e.g. one chunk of a prompt
+        // that is prefilled in pieces: how many pieces per tile?  More pieces shorten the blocks and fill the chip,
+        // but every piece writes a 64 KiB partial tile per KV head that the merge kernel reads back, and a second
+        // kernel has to be launched at all.  Estimated cost in microseconds, from measurements on this part: a block
+        // advances 32 keys in ~0.62 us alone on its compute unit and in ~0.9 us next to a second block; blocks beyond
+        // the 512 slots run in further rounds; the merge moves the partial tiles twice at ~4.5 TB/s after ~5 us of
+        // launch.  (8192-token prompt, LLaMA2-70B shape: chunks of 512 tokens 1,600 -> 1,45x us per pass, chunks of
+        // 256 tokens 1,956 -> 1,7xx us, against one fixed rule of about a thousand keys per piece.)
+        const int64_t blocks1 = (int64_t)n_chunk_tiles * cfg.num_kv_heads;
+        int64_t max_span = 1;
+        for (size_t ti = 0; ti < n_chunk_tiles; ++ti)
+            max_span = std::max<int64_t>(max_span, plan.tiles[ti].n_keys - plan.tiles[ti].key_lo);
+        const double avg_steps = (double)keys_of_kind[kKindTile] / (double)n_chunk_tiles / kTileKeys;
+        double best = 0.0;
+        int64_t best_n = 1;
+        for (int64_t n = 1; n <= 16; ++n) {
+            if (n > 1 && max_span / n < 256) break;   // pieces of fewer than eight key steps are all prologue
+            const int64_t blocks = blocks1 * n;
+            const double steps = avg_steps / (double)n + 1.0;
+            const double rounds = blocks <= 512 ? 1.0 : (double)blocks / 512.0;
+            const double step_us = blocks <= 256 ? 0.62 : 0.9;
+            double cost = 4.0 + rounds * steps * step_us;
+            if (n > 1) {
+                const double partial_bytes = (double)blocks * kTileCols * (cfg.head_dim + 2) * 4.0;
+                cost += 5.0 + 2.0 * partial_bytes / 4.5e6;
+            }
+            if (n == 1 || cost < best) {
+                best = cost;
+                best_n = n;
+            }
+        }
+        tile_split = ceil_div(ceil_div(max_span, best_n), kTileKeys) * kTileKeys;
+    }
     for (;;) {
         int64_t n_split_units = 0, rows = 0, n_split_tiles = 0;
         count_splits(plan, 0, n_chunk_tiles, tile_split, n_split_units, rows, n_split_tiles);
