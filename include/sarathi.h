@@ -120,8 +120,6 @@ const char *sarathi_last_error(const sarathi_handle *handle);
  * "decode_blocks_per_cu" (launches that hold decodes / 16-column tiles only: 1 = one block per compute unit, so
  * that blocks start longest first as units fall free, which shortens the tail of small batches; 2 = as many as fit;
  * -1 = automatic: one for up to 1024 blocks),
- * "merge_in_kernel" (key ranges cut into pieces: 0 = a second small kernel merges the pieces, 1 = the piece that
- * finishes last merges them inside the attention launch; results are bitwise reproducible either way),
  * "inline_append" (0/1: sarathi_kv_append sends up to 224 page records in its kernel's arguments instead of
  * letting the blocks read them from the pinned buffer), "lds_pad_kb" (diagnostic: KiB of unused LDS per
  * attention block, which lowers the number of blocks a compute unit holds),
@@ -200,8 +198,8 @@ sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
  * nothing (no hipMalloc / hipHostMalloc / hipFree, no stream or event creation) and enqueues kernels only; it
  * records no timing events ("time_kernels" is ignored) and treats option "interleave" = 1 as 2.
  *
- * Limits: the packed plan (64 bytes per tile of 16 decode columns or 128 chunk columns, 4 bytes per work item)
- * must fit into 96 KiB, else SARATHI_ECAPACITY (roughly 1,400 sequences); 16 MiB of partial rows (4,096 rows at
+ * Limits: the packed plan (48 bytes per tile of 16 decode columns or 128 chunk columns, 4 bytes per work item)
+ * must fit into 96 KiB, else SARATHI_ECAPACITY (roughly 1,800 sequences); 16 MiB of partial rows (4,096 rows at
  * 8 KV heads x 128 channels; key ranges are cut less finely when that is short, never refused);
  * num_kv_heads * head_dim * 4 bytes per partial row must leave room for 256 rows, else SARATHI_ECAPACITY.
  * Every call on a GPU shares that GPU's array: two calls that overlap in time on one GPU (two streams, two

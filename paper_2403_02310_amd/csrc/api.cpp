@@ -164,18 +164,15 @@ void timing_end(sarathi_handle *h, int kind, int idx, hipStream_t s) {
     if (hipEventRecord(h->timing_pool[kind][idx].second, s) == hipSuccess) h->timing_used[kind] = (size_t)idx + 1;
 }
 
-// Attention metadata, packed back to back at `dst`: tile descriptors, work units, merge units, and the arrival
-// counters of the split tiles ([split tile][KV head], zeros: they reach the device with the plan, so every launch
-// starts from zero whatever the memory held).
+// Attention metadata, packed back to back at `dst`: tile descriptors, work units, merge units.
 struct AttnMetaOffsets {
-    size_t units, reduce, counters, total;
+    size_t units, reduce, total;
 };
-AttnMetaOffsets attn_meta_offsets(const Plan &pl, int num_kv_heads) {
+AttnMetaOffsets attn_meta_offsets(const Plan &pl) {
     AttnMetaOffsets o;
     o.units = align_up(sizeof(TileDesc) * pl.tiles.size(), 16);
     o.reduce = o.units + sizeof(uint32_t) * pl.units.size();
-    o.counters = align_up(o.reduce + sizeof(uint32_t) * pl.reduce_units.size(), 16);
-    o.total = align_up(o.counters + sizeof(int32_t) * (size_t)pl.num_split_tiles * num_kv_heads, 16);
+    o.total = align_up(o.reduce + sizeof(uint32_t) * pl.reduce_units.size(), 16);
     return o;
 }
 template <typename T>
@@ -186,7 +183,6 @@ void pack_attn_meta(char *dst, const Plan &pl, const AttnMetaOffsets &o) {
     copy_vector(dst, pl.tiles);
     copy_vector(dst + o.units, pl.units);
     copy_vector(dst + o.reduce, pl.reduce_units);
-    std::memset(dst + o.counters, 0, o.total - o.counters);
 }
 
 bool resident_plan_matches(const sarathi_handle *h, const int32_t *q_len, const int32_t *ctx_len, int32_t n,
@@ -204,7 +200,7 @@ sarathi_status enqueue_attention(sarathi_handle *h, char *dev, float *part_ml, f
                                  const int32_t *block_table, const void *q, const void *k_cache, const void *v_cache,
                                  int64_t num_pages, float sm_scale, void *out, hipStream_t s, bool instrumented) {
     const Plan &pl = h->plan;
-    const AttnMetaOffsets mo = attn_meta_offsets(pl, h->cfg.num_kv_heads);
+    const AttnMetaOffsets mo = attn_meta_offsets(pl);
     const size_t units_off = mo.units, reduce_off = mo.reduce;
     void *stream = static_cast<void *>(s);
     hipError_t e;
@@ -221,9 +217,6 @@ sarathi_status enqueue_attention(sarathi_handle *h, char *dev, float *part_ml, f
     m.num_tile_reduce_units = pl.num_tile_reduce_units;
     m.part_ml = part_ml;
     m.part_o = part_o;
-    const bool merge_in_kernel = h->opt.merge_in_kernel != 0 && pl.num_split_tiles > 0;
-    m.merge_cnt = merge_in_kernel ? reinterpret_cast<int32_t *>(dev + mo.counters) : nullptr;
-    if (merge_in_kernel) h->resident_ws = nullptr;  // the launch uses the counters up: a repeated call brings the plan again
     m.sched = sched;
     m.window = (int32_t)h->opt.window;
     m.lds_pad_bytes = (int32_t)h->opt.lds_pad_kb * 1024;
@@ -256,7 +249,7 @@ sarathi_status enqueue_attention(sarathi_handle *h, char *dev, float *part_ml, f
     // has both they run side by side: the chunk kernel is forked onto a second stream, where the
     // merge of its own split tiles follows it (hidden behind the longer wave kernel).
     const bool both = pl.num_tile_units > 0 && (int32_t)pl.units.size() > pl.num_tile_units;
-    const bool fork = both && h->opt.interleave == 1 && instrumented && !merge_in_kernel;
+    const bool fork = both && h->opt.interleave == 1 && instrumented;
     if (fork && !h->side_stream) {
         e = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking);
         if (e != hipSuccess) return hip_fail(h, "hipStreamCreate(side)", e);
@@ -294,7 +287,7 @@ sarathi_status enqueue_attention(sarathi_handle *h, char *dev, float *part_ml, f
     }
     timing_end(h, 1, t1, s);
     if (e != hipSuccess) return hip_fail(h, "launch attention", e);
-    if (!merge_in_kernel && m.num_reduce_units > merged_on_side) {
+    if (m.num_reduce_units > merged_on_side) {
         const int t2 = instrumented ? timing_begin(h, 2, s) : -1;
         e = (hipError_t)launch_reduce(h->cfg, m, out, merged_on_side, m.num_reduce_units - merged_on_side, stream);
         timing_end(h, 2, t2, s);
@@ -394,11 +387,6 @@ extern "C" sarathi_status sarathi_set_option(sarathi_handle *h, const char *name
     if (std::strcmp(name, "lds_pad_kb") == 0) {
         if (value < 0 || value > 96) return fail(h, SARATHI_EINVAL, "lds_pad_kb must be 0 .. 96");
         h->opt.lds_pad_kb = value;
-        return SARATHI_OK;
-    }
-    if (std::strcmp(name, "merge_in_kernel") == 0) {
-        if (value < 0 || value > 1) return fail(h, SARATHI_EINVAL, "merge_in_kernel must be 0 or 1");
-        h->opt.merge_in_kernel = value;
         return SARATHI_OK;
     }
     if (std::strcmp(name, "resident_chunks") == 0) {
@@ -527,7 +515,7 @@ extern "C" sarathi_status sarathi_kv_append(sarathi_handle *h, const void *k_new
     h->resident_ws = nullptr;
     if (h->opt.plan_at_append) {
         plan_attention(h->cfg, h->opt, h->ws, q_start, q_len, ctx_len, num_seqs, h->plan);
-        const AttnMetaOffsets o = attn_meta_offsets(h->plan, h->cfg.num_kv_heads);
+        const AttnMetaOffsets o = attn_meta_offsets(h->plan);
         const size_t attn_off = align_up(used, 256);
         if (attn_off + o.total <= h->staging_bytes) {
             pack_attn_meta(reinterpret_cast<char *>(units) + attn_off, h->plan, o);
@@ -592,7 +580,7 @@ extern "C" sarathi_status sarathi_hybrid_attention(sarathi_handle *h, const void
         int slot;
         if ((st = acquire_slot(h, s, &slot)) != SARATHI_OK) return st;
         SlotGuard guard{h, slot, s};
-        const AttnMetaOffsets o = attn_meta_offsets(h->plan, h->cfg.num_kv_heads);
+        const AttnMetaOffsets o = attn_meta_offsets(h->plan);
         if (o.total > h->staging_bytes) return fail(h, SARATHI_ECAPACITY, "internal: metadata exceeds staging buffer");
         char *host = static_cast<char *>(h->staging[slot]);
         pack_attn_meta(host, h->plan, o);
@@ -626,11 +614,11 @@ extern "C" sarathi_status sarathi_hybrid_attention_noalloc(sarathi_handle *h, co
         return fail(h, SARATHI_ECAPACITY, "allocation-free entry point: num_kv_heads * head_dim is too large for the built-in scratch");
     h->resident_ws = nullptr;  // h->plan is about to be overwritten
     plan_attention(h->cfg, h->opt, lay, q_start, q_len, ctx_len, num_seqs, h->plan);
-    const AttnMetaOffsets o = attn_meta_offsets(h->plan, h->cfg.num_kv_heads);
+    const AttnMetaOffsets o = attn_meta_offsets(h->plan);
     if (o.total > kStaticMetaBytes || o.total > h->noalloc_meta.size()) {
         char buf[200];
         snprintf(buf, sizeof buf, "allocation-free entry point: the batch's plan needs %zu bytes of metadata, the built-in "
-                 "scratch holds %zu (about %zu sequences or 128-column tiles)", o.total, kStaticMetaBytes, kStaticMetaBytes / 68);
+                 "scratch holds %zu (about %zu sequences or 128-column tiles)", o.total, kStaticMetaBytes, kStaticMetaBytes / 52);
         return fail(h, SARATHI_ECAPACITY, buf);
     }
     StaticScratch sc;

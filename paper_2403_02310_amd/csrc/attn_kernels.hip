@@ -23,7 +23,8 @@
 //
 // Chunk-tile path (prefill chunks).  A workgroup of four wavefronts owns 128 columns of one
 // sequence (32 per wave) and walks the key range in 32-key tiles staged once per workgroup in
-// LDS (double-buffered, one barrier per tile), so K/V are fetched from L2/HBM once per 128
+// LDS (rings of four K tiles and four V tiles filled by direct global -> LDS loads, K three tiles
+// ahead of the step and V two; one barrier per tile), so K/V are fetched from L2/HBM once per 128
 // columns instead of once per 16.  The contractions use v_mfma_f32_32x32x16_bf16, again in
 // transposed form with the K rows of a tile permuted (MFMA row 16u+8a+4h+b <-> key 16u+8h+4a+b)
 // so that accumulator lane (h, n) holds, for column n, keys 8h..8h+7 of page u in registers
@@ -42,9 +43,14 @@
 // Split-KV.  A tile whose key range was cut into pieces has every piece write its partial
 // (reference maximum, sum, unnormalised output) triple; a second, small kernel merges the
 // pieces of each tile in index order, so the result is bitwise reproducible.  (Merging inside
-// the attention kernel by the last piece to finish was tried and dropped: on this multi-die
-// part the device-scope release/acquire fences it needs write back and invalidate whole L2s
-// and made the kernel several times slower.)
+// the attention kernel by the last piece to finish was built twice and dropped on its timings.
+// With device-scope release/acquire fences every block writes back and invalidates a whole L2 of
+// this multi-die part: several times slower.  Without fences, the partial rows themselves written and
+// read with device-scope accesses, whole 512-byte rows at a time, and a piece that finds the others
+// done merging without publishing: correct, and still slower than the second kernel in every case
+// measured (a 512-token chunk alone 57 us against 40 + 13, chunks of 256 tokens 1,866 us per prompt
+// against 1,717), because such accesses bypass the L2 that serves the second kernel's reads, and
+// ONE block per tile reads what 16 blocks of the merge kernel read in parallel.)
 //
 // Masking is by select: keys beyond a column's position (causal mask inside a chunk, section
 // 4.1 of the paper) or beyond the item's key range get score -inf; V of slots at or beyond
@@ -85,7 +91,6 @@ struct AttnParams {
     int32_t num_tile_units;  // units [0, num_tile_units) are 128-column chunk tiles (one block each)
     int32_t num_units;       // the rest are 16-column wave tiles (one block each as well)
     float scale_log2;        // sm_scale * log2(e): the softmax runs in base 2
-    int32_t *merge_cnt;      // arrival counters [split tile][KV head], zero at launch; null: a second kernel merges split tiles
     int32_t *sched;          // scheduling words of the run-time role assignment (else unused)
     int32_t window;          // sliding window: a query at position p sees keys p-window+1 .. p; 0 = all keys up to p
 };
@@ -113,35 +118,6 @@ __device__ __forceinline__ bf16x8 load_bf16x8(const uint16_t *p) {
 }
 __device__ __forceinline__ bf16x8 load_bf16x8_stream(const uint16_t *p) {
     return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)));
-}
-
-// ---- split tiles merged inside the launch -------------------------------------------------------------------
-// The pieces of a split tile hand their partial (maximum, sum, unnormalised output) rows to whichever piece
-// finishes last, inside one launch and possibly across dies.  Partial rows are therefore written and read with
-// relaxed atomic accesses of device scope, 64 bits at a time: such an access is performed at the level all
-// compute units share (it does not linger in a die's cache), so the only ordering left to establish is "every
-// store of this block has been performed before the block counts itself in", which a wait for the block's
-// outstanding stores plus a block barrier gives.  Device-scope release/acquire FENCES, the textbook way, write
-// back and invalidate a whole L2 each time on this multi-die part and made the kernel several times slower when
-// every block used them.  No piece ever waits for another: the last one to count itself in merges all pieces in
-// index order (bitwise reproducible, whoever is last), the others are done.
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-__device__ __forceinline__ void agent_store2(float *p, float a, float b) {
-    const uint64_t bits = (uint64_t)__builtin_bit_cast(uint32_t, a) | ((uint64_t)__builtin_bit_cast(uint32_t, b) << 32);
-    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ f32x2 agent_load2(const float *p) {
-    const uint64_t bits = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return f32x2{__builtin_bit_cast(float, (uint32_t)bits), __builtin_bit_cast(float, (uint32_t)(bits >> 32))};
-}
-// Called by every thread of a block after its partial stores.  True (in every thread) in the block that completes
-// the tile's count.  `lds_word` is a word of LDS nobody reads any more.
-__device__ __forceinline__ bool piece_arrives_last(int32_t *counter, int n_pieces, int32_t *lds_word) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's partial rows have been performed
-    __syncthreads();
-    if (threadIdx.x == 0) *lds_word = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    return *lds_word == n_pieces - 1;
 }
 
 template <int D>
@@ -381,93 +357,52 @@ __device__ __forceinline__ void wave16_path(const AttnParams &p, const TileDesc 
     constexpr int CH = D / 16;
     const int mc = threadIdx.x >> 4;
     const int ch0 = (threadIdx.x & 15) * CH;
-    const bool col_ok = mc < it.n_cols;
-    const UnitRange whole = unit_range(it, split);
-    const bool merge_here = whole.part_row >= 0 && p.merge_cnt != nullptr;  // block-uniform
-    if (!col_ok && !merge_here) return;
+    if (mc >= it.n_cols) return;
+    float m_w[4], m_max = kNegSentinel;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        m_w[w] = merge_lds[MS::kOutFloats + (w * kWaveCols + mc) * 2];
+        m_max = fmaxf(m_max, m_w[w]);
+    }
     float acc[CH];
 #pragma unroll
     for (int j = 0; j < CH; ++j) acc[j] = 0.f;
-    float l_tot = 0.f, m_max = kNegSentinel;
-    if (col_ok) {
-        float m_w[4];
+    float l_tot = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            m_w[w] = merge_lds[MS::kOutFloats + (w * kWaveCols + mc) * 2];
-            m_max = fmaxf(m_max, m_w[w]);
-        }
+    for (int w = 0; w < 4; ++w) {
+        const float wt = __builtin_amdgcn_exp2f(m_w[w] - m_max);
+        l_tot += wt * merge_lds[MS::kOutFloats + (w * kWaveCols + mc) * 2 + 1];
+        const float *o_w = merge_lds + (w * kWaveCols + mc) * MS::kColStride + ch0;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float wt = __builtin_amdgcn_exp2f(m_w[w] - m_max);
-            l_tot += wt * merge_lds[MS::kOutFloats + (w * kWaveCols + mc) * 2 + 1];
-            const float *o_w = merge_lds + (w * kWaveCols + mc) * MS::kColStride + ch0;
+        for (int j = 0; j < CH; j += 4) {
+            const f32x4 o4 = *reinterpret_cast<const f32x4 *>(o_w + j);
 #pragma unroll
-            for (int j = 0; j < CH; j += 4) {
-                const f32x4 o4 = *reinterpret_cast<const f32x4 *>(o_w + j);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) acc[j + i] += wt * o4[i];
-            }
+            for (int i = 0; i < 4; ++i) acc[j + i] += wt * o4[i];
         }
     }
-    const int mcol = it.col_begin + (col_ok ? mc : 0);
+    const int mcol = it.col_begin + mc;
     const int mrow = mcol / G;
     const int mhead = kvh * G + (mcol - mrow * G);
-    uint16_t *op = p.out + ((int64_t)(q_start + mrow) * p.num_q_heads + mhead) * D + ch0;
-    auto write_out = [&](float inv) {
+    const UnitRange whole = unit_range(it, split);
+    if (whole.part_row < 0) {
+        const float inv = 1.0f / l_tot;
+        uint16_t *op = p.out + ((int64_t)(q_start + mrow) * p.num_q_heads + mhead) * D + ch0;
 #pragma unroll
         for (int j = 0; j < CH; j += 4) {
             const f32x4 o = {acc[j] * inv, acc[j + 1] * inv, acc[j + 2] * inv, acc[j + 3] * inv};
             *reinterpret_cast<u32x2 *>(op + j) = __builtin_bit_cast(u32x2, __builtin_convertvector(o, bf16x4));
         }
-    };
-    if (whole.part_row < 0) {
-        write_out(1.0f / l_tot);
         return;
     }
     // Tile split across blocks: this block's (reference maximum, sum, unnormalised output).
-    const int64_t prow = ((int64_t)(whole.part_row + (col_ok ? mc : 0)) * p.num_kv_heads + kvh);
+    const int64_t prow = ((int64_t)(whole.part_row + mc) * p.num_kv_heads + kvh);
     float *po = p.part_o + prow * D + ch0;
-    if (!merge_here) {  // merged by the second kernel
 #pragma unroll
-        for (int j = 0; j < CH; j += 4) *reinterpret_cast<f32x4 *>(po + j) = f32x4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
-        if ((threadIdx.x & 15) == 0) {
-            p.part_ml[prow * 2 + 0] = m_max;
-            p.part_ml[prow * 2 + 1] = l_tot;
-        }
-        return;
+    for (int j = 0; j < CH; j += 4) *reinterpret_cast<f32x4 *>(po + j) = f32x4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
+    if ((threadIdx.x & 15) == 0) {
+        p.part_ml[prow * 2 + 0] = m_max;
+        p.part_ml[prow * 2 + 1] = l_tot;
     }
-    if (col_ok) {
-#pragma unroll
-        for (int j = 0; j < CH; j += 2) agent_store2(po + j, acc[j], acc[j + 1]);
-        if ((threadIdx.x & 15) == 0) agent_store2(p.part_ml + prow * 2, m_max, l_tot);
-    }
-    const bool last = piece_arrives_last(p.merge_cnt + (int64_t)it.merge_slot * p.num_kv_heads + kvh, it.n_splits,
-                                         reinterpret_cast<int32_t *>(merge_lds));
-    if (!last || !col_ok) return;
-    // Every piece of the tile has arrived: merge them in index order.
-    const int64_t prow0 = ((int64_t)(it.part_row0 + mc) * p.num_kv_heads + kvh);
-    const int64_t piece_stride = (int64_t)it.n_cols * p.num_kv_heads;
-    m_max = kNegSentinel;
-#pragma unroll 4
-    for (int i = 0; i < it.n_splits; ++i) m_max = fmaxf(m_max, agent_load2(p.part_ml + (prow0 + i * piece_stride) * 2)[0]);
-#pragma unroll
-    for (int j = 0; j < CH; ++j) acc[j] = 0.f;
-    l_tot = 0.f;
-#pragma unroll 2
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t pr = prow0 + i * piece_stride;
-        const f32x2 ml = agent_load2(p.part_ml + pr * 2);
-        const float wt = __builtin_amdgcn_exp2f(ml[0] - m_max);
-        l_tot += wt * ml[1];
-        const float *pi = p.part_o + pr * D + ch0;
-#pragma unroll
-        for (int j = 0; j < CH; j += 2) {
-            const f32x2 o2 = agent_load2(pi + j);
-            acc[j] += wt * o2[0];
-            acc[j + 1] += wt * o2[1];
-        }
-    }
-    write_out(1.0f / l_tot);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1008,75 +943,21 @@ __device__ __forceinline__ void chunk_tile_path(const AttnParams &p, const TileD
         return;
     }
     // Split tile: publish this piece's (reference maximum, sum, unnormalised output).
-    const int64_t prow = ((int64_t)(ur.part_row + (col_valid ? wcol : 0)) * p.num_kv_heads + kvh);
-    float *po = p.part_o + prow * D + h * 4;
-    if (!p.merge_cnt) {  // merged by the second kernel
-        if (col_valid) {
-#pragma unroll
-            for (int c = 0; c < NB; ++c)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
-                    *reinterpret_cast<f32x4 *>(po + c * 32 + q4 * 8) = o;
-                }
-            if (h == 0) {
-                p.part_ml[prow * 2 + 0] = m_ref;
-                p.part_ml[prow * 2 + 1] = l;
-            }
-        }
-        return;
-    }
     if (col_valid) {
+        const int64_t prow = ((int64_t)(ur.part_row + wcol) * p.num_kv_heads + kvh);
+        float *po = p.part_o + prow * D + h * 4;
 #pragma unroll
         for (int c = 0; c < NB; ++c)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                agent_store2(po + c * 32 + q4 * 8, oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1]);
-                agent_store2(po + c * 32 + q4 * 8 + 2, oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]);
+                f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
+                *reinterpret_cast<f32x4 *>(po + c * 32 + q4 * 8) = o;
             }
-        if (h == 0) agent_store2(p.part_ml + prow * 2, m_ref, l);
-    }
-    // the ring is dead once every wave is behind the barrier inside: its first word carries the count
-    const bool last = piece_arrives_last(p.merge_cnt + (int64_t)it.merge_slot * p.num_kv_heads + kvh, it.n_splits,
-                                         reinterpret_cast<int32_t *>(smem));
-    if (!last || !col_valid) return;
-    // Every piece of the tile has arrived: merge them in index order; a lane merges the channels it owns.
-    const int64_t prow0 = ((int64_t)(it.part_row0 + wcol) * p.num_kv_heads + kvh);
-    const int64_t piece_stride = (int64_t)it.n_cols * p.num_kv_heads;
-    float m_max = kNegSentinel;
-#pragma unroll 4
-    for (int i = 0; i < it.n_splits; ++i) m_max = fmaxf(m_max, agent_load2(p.part_ml + (prow0 + i * piece_stride) * 2)[0]);
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
-    float l_sum = 0.f;
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t pr = prow0 + i * piece_stride;
-        const f32x2 ml = agent_load2(p.part_ml + pr * 2);
-        const float wt = __builtin_amdgcn_exp2f(ml[0] - m_max);
-        l_sum += wt * ml[1];
-        const float *pi = p.part_o + pr * D + h * 4;
-#pragma unroll
-        for (int c = 0; c < NB; ++c)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x2 a = agent_load2(pi + c * 32 + q4 * 8), b = agent_load2(pi + c * 32 + q4 * 8 + 2);
-                oacc[c][q4 * 4 + 0] += wt * a[0];
-                oacc[c][q4 * 4 + 1] += wt * a[1];
-                oacc[c][q4 * 4 + 2] += wt * b[0];
-                oacc[c][q4 * 4 + 3] += wt * b[1];
-            }
-    }
-    const float inv = 1.0f / l_sum;
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            f32x4 o = {oacc[c][q4 * 4 + 0], oacc[c][q4 * 4 + 1], oacc[c][q4 * 4 + 2], oacc[c][q4 * 4 + 3]};
-            const bf16x4 o4 = __builtin_convertvector(o * inv, bf16x4);
-            *reinterpret_cast<u32x2 *>(op + c * 32 + q4 * 8) = __builtin_bit_cast(u32x2, o4);
+        if (h == 0) {
+            p.part_ml[prow * 2 + 0] = m_ref;
+            p.part_ml[prow * 2 + 1] = l;
         }
+    }
 }
 
 // Chunk tiles: one block per (unit, KV head); one wavefront per SIMD so that the pipelined
@@ -1508,7 +1389,6 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *q
     p.num_tile_units = m.num_tile_units;
     p.num_units = m.num_units;
     p.scale_log2 = sm_scale * 1.4426950408889634f;
-    p.merge_cnt = m.merge_cnt;
     p.sched = nullptr;
     p.window = m.window;
     const bool stream_kv = m.stream_kv != 0;

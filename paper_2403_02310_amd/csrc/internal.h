@@ -47,10 +47,8 @@ struct TileDesc {
     int32_t q_start;
     int32_t q_len;
     int32_t ctx_len;
-    int32_t merge_slot;   // index of this tile among the split tiles (row of the arrival counters), -1 if n_splits == 1
-    int32_t reserved[3];
 };
-static_assert(sizeof(TileDesc) == 64, "TileDesc is copied to the device as raw bytes");
+static_assert(sizeof(TileDesc) == 48, "TileDesc is copied to the device as raw bytes");
 
 // A work unit = (tile index, split index) packed into 32 bits.
 constexpr int kUnitTileBits = 22;
@@ -103,8 +101,6 @@ struct Options {
                                     // all at once); -1 = one for up to 1024 blocks, two beyond
     int64_t inline_append = 1;      // KV append: up to 224 page records travel in the kernel's arguments (else all are read from the pinned buffer)
     int64_t lds_pad_kb = 0;         // diagnostic only: KiB of unused LDS added to every attention block
-    int64_t merge_in_kernel = 0;    // split tiles: 1 = the last piece of a tile to finish merges all of them inside the attention
-                                    // launch (arrival counters), 0 = a second, small kernel merges them
     int64_t resident_chunks = -1;   // one-launch mode: blocks take their role (chunk or wave tiles) when they start, so that
                                     // a compute unit holds at most one chunk block while decode work remains
                                     // (-1 = when there are more chunk blocks than compute units, 0 = never, 1 = always)
@@ -166,8 +162,6 @@ struct AttnMeta {
     int32_t num_tile_reduce_units;   // leading entries of reduce_units that belong to chunk tiles
     float *part_ml;              // dev
     float *part_o;               // dev
-    int32_t *merge_cnt;          // dev [num_split_tiles][Hkv] arrival counters, zero at launch (they travel with the plan);
-                                 // null: the pieces are merged by launch_reduce instead
     int32_t *sched;              // dev, kSchedBytes
     int32_t window;              // sliding window in keys, 0 = none
     int32_t stream_kv;           // 1: the wave tiles' K/V loads carry the streaming hint

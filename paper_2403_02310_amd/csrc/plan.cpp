@@ -38,8 +38,7 @@ WorkspaceLayout make_workspace_layout(const sarathi_config &cfg) {
     // a split tile has at least 2 pieces of n_cols rows: sum over split tiles of ceil(n_cols/8) <= rows/16 + tiles
     w.max_reduce_units = (int32_t)std::min<int64_t>(kMaxPartRows / (2 * kReduceCols) + kMaxSplitUnits / 2, INT32_MAX / 64);
     const size_t attn_meta = sizeof(TileDesc) * (size_t)w.max_tiles +
-                             sizeof(uint32_t) * ((size_t)w.max_units + (size_t)w.max_reduce_units) +
-                             sizeof(int32_t) * (size_t)(kMaxSplitUnits / 2) * cfg.num_kv_heads + 64;  // + arrival counters
+                             sizeof(uint32_t) * ((size_t)w.max_units + (size_t)w.max_reduce_units) + 64;
     const size_t append_meta = sizeof(AppendUnit) * (size_t)max_append_units(cfg) + 64;
     size_t off = 0;
     w.meta = off;
@@ -111,13 +110,11 @@ void emit_units(Plan &plan, size_t first, size_t last, int64_t split_keys, std::
         if (t.n_splits > 1) {
             t.part_row0 = plan.num_part_rows;
             plan.num_part_rows += t.n_splits * t.n_cols;
-            t.merge_slot = plan.num_split_tiles;
             plan.num_split_tiles++;
             for (int32_t c0 = 0, grp = 0; c0 < t.n_cols; c0 += kReduceCols, ++grp)
                 plan.reduce_units.push_back(pack_unit((uint32_t)ti, (uint32_t)grp));
         } else {
             t.part_row0 = -1;
-            t.merge_slot = -1;
         }
         for (int32_t i = 0; i < t.n_splits; ++i) {
             scratch.push_back(pack_unit((uint32_t)ti, (uint32_t)i));

@@ -134,11 +134,10 @@ int launch_attention(const sarathi_config &cfg, const AttnMeta &m, const void *,
         const int n_pages = (t.ctx_len + kPageSize - 1) / kPageSize;
         g_sink += (uint64_t)m.block_table[(int64_t)t.seq * m.max_blocks + n_pages - 1];  // last table entry the kernel may read
         if (t.n_splits > 1) {
-            CHECK(t.part_row0 >= 0 && t.merge_slot >= 0);
+            CHECK(t.part_row0 >= 0);
             const int64_t last_row = (int64_t)t.part_row0 + (int64_t)t.n_splits * t.n_cols - 1;
             m.part_o[(last_row * H + H - 1) * D + D - 1] = 0.f;
             m.part_ml[(last_row * H + H - 1) * 2 + 1] = 0.f;
-            if (m.merge_cnt) CHECK(m.merge_cnt[(int64_t)t.merge_slot * H + H - 1] == 0);   // counters arrive as zeros
         } else {
             CHECK(t.part_row0 == -1);
         }
@@ -210,7 +209,6 @@ static void drive_attention_host_paths(std::mt19937_64 &rng) {
         if (it % 3 == 1) CHECK(sarathi_set_option(h, "split_keys", 64) == SARATHI_OK && sarathi_set_option(h, "tile_split_keys", 64) == SARATHI_OK);
         if (it % 3 == 2) CHECK(sarathi_set_option(h, "window", rnd(1, 500)) == SARATHI_OK);
         if (it % 4 == 3) CHECK(sarathi_set_option(h, "resident_chunks", 1) == SARATHI_OK);
-        if (it % 7 == 6) CHECK(sarathi_set_option(h, "merge_in_kernel", 0) == SARATHI_OK);
         const int64_t num_pages = pages_needed + 3;
         std::vector<int32_t> bt((size_t)S * max_blocks, -1);
         int64_t next = 0;
@@ -229,7 +227,7 @@ static void drive_attention_host_paths(std::mt19937_64 &rng) {
         sarathi::g_num_tokens = T;
         CHECK(sarathi_kv_append(h, k_new.data(), v_new.data(), kc.data(), vc.data(), bt.data(), qs.data(), ql.data(), cl.data(), S,
                                 (int32_t)T, num_pages, ws, nullptr) == SARATHI_OK);
-        for (int rep = 0; rep < 2; ++rep)   // the second call finds no resident plan when the first used its counters up
+        for (int rep = 0; rep < 2; ++rep)   // the second call finds the plan the append brought still resident
             CHECK(sarathi_hybrid_attention(h, q.data(), kc.data(), vc.data(), bt.data(), qs.data(), ql.data(), cl.data(), S, (int32_t)T,
                                            num_pages, 0.1f, out.data(), ws, nullptr) == SARATHI_OK);
         CHECK(sarathi_hybrid_attention_noalloc(h, q.data(), kc.data(), vc.data(), bt.data(), qs.data(), ql.data(), cl.data(), S,
