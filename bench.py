@@ -219,6 +219,72 @@ def run_token_budget(args) -> int:
     return 0
 
 
+def run_decode_probe(args) -> int:
+    """What bounds the decode path, measured with the library's own kernel on synthetic decode-only batches:
+    (a) N identical decodes of CTX keys (N x 8 blocks of equal length): the rate one block reaches alone, the rate per
+    compute unit with one and with two blocks on it, and the chip-wide streaming ceiling;
+    (b) N decodes of mixed lengths (uniform in [256, 4096] and the lognormal recipe) at one and at two blocks per
+    compute unit: where starting blocks longest-first as units fall free beats having all of them resident."""
+    import torch
+    from paper_2403_02310_amd import binding, workloads as wl
+    s = wl.MISTRAL_7B
+    reps = max(10, min(args.steps, 30))
+
+    def attention_us(b, opts):
+        h = binding.Handle(s.num_q_heads, s.num_kv_heads, s.head_dim, max_tokens=2048, max_seqs=max(128, b.num_seqs),
+                           max_blocks_per_seq=b.max_blocks_per_seq)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        g = torch.Generator(device="cuda").manual_seed(1)
+        rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=g).to(torch.bfloat16)
+        pools = [(rnd(b.num_pages, s.num_kv_heads, 16, s.head_dim), rnd(b.num_pages, s.num_kv_heads, s.head_dim, 16)) for _ in range(3)]
+        q = rnd(b.num_tokens, s.num_q_heads, s.head_dim)
+        out = torch.empty_like(q)
+        bt = torch.from_numpy(b.block_table).cuda()
+        h.set_option("time_kernels", 1)
+        for i in range(5 + reps):
+            if i == 5:
+                h.kernel_times()
+            kc, vc = pools[i % 3]     # three pools in turn: no launch finds its keys in the last-level cache
+            h.hybrid_attention(q, kc, vc, bt, b.q_start, b.q_len, b.ctx_len, b.sm_scale, out)
+        torch.cuda.synchronize()
+        kt = h.kernel_times()
+        return kt.attention_ms * 1e3 / kt.attention_launches
+
+    equal = []
+    for n, ctx in ((4, 8192), (8, 8192), (16, 8192), (24, 8192), (32, 8192), (48, 8192), (64, 8192), (128, 4096), (256, 2048)):
+        b = wl._make("equal", s, [1] * n, [ctx] * n, 5, slack=1.0)
+        row = {"decodes": n, "ctx": ctx, "blocks": n * s.num_kv_heads}
+        for name, per_cu in (("two_per_cu", 2), ("one_per_cu", 1)):
+            us = attention_us(b, {"decode_blocks_per_cu": per_cu, "split_keys": 1 << 20})
+            row[name] = {"us": us, "TBps": b.kv_bytes() / us / 1e6, "GBps_per_block": b.kv_bytes() / us / 1e3 / (n * s.num_kv_heads)}
+        equal.append(row)
+    mixed = []
+    for n in (16, 32, 48, 64, 96, 128, 192, 256):
+        rng = np.random.default_rng([7, n])
+        for kind in ("uniform[256,4096]", "lognormal(1024,0.8)"):
+            if kind.startswith("uniform"):
+                ctx = rng.integers(256, 4097, size=n)
+            else:
+                ctx = np.clip(np.rint(np.exp(np.log(1024.0) + 0.8 * rng.standard_normal(n))), 64, 8192).astype(np.int32)
+            b = wl._make("mixed", s, [1] * n, ctx, 9, slack=1.0)
+            row = {"decodes": n, "lengths": kind, "MB": b.algorithmic_bytes() / 1e6}
+            for name, per_cu in (("two_per_cu", 2), ("one_per_cu", 1)):
+                us = attention_us(b, {"decode_blocks_per_cu": per_cu})
+                row[name] = {"us": us, "hbm_frac": b.algorithmic_bytes() / us / 1e3 / HBM_PEAK_GBS}
+            mixed.append(row)
+    best = max(r["two_per_cu"]["TBps"] for r in equal)
+    print(json.dumps({
+        "metric": "decode streaming probe: highest K/V rate of equal-length decode batches", "value": best * 1e3, "unit": "GB/s",
+        "n_gpus": 1, "steps": reps, "warmup": 5, "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "decode_probe: Mistral-7B attention shape, decode-only batches, compact pools, three pool copies rotated"},
+        "roofline": {"bound": "hbm", "kernel": "attn_wave_kernel", "achieved": best * 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": best * 1e3 / HBM_PEAK_GBS, "traffic": None},
+        "equal_length": equal, "mixed_length": mixed}))
+    return 0
+
+
 def run_linear(args) -> int:
     """Linear layers of one transformer layer against the number of tokens in the batch (section 3.1): the four
     models of Table 1, one GPU's share under the paper's tensor-parallel degree."""
@@ -277,7 +343,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2",
                     help="c2 (default), c3, c4, c5, <cN>_chunks, <cN>_decodes, c5_sweep (one 8192-token prompt prefilled in "
                          "chunks of 64 ... 2048 and in one shot), serve (serving loop over a request trace), budget "
-                         "(token-budget profile), linear (linear layers against the number of tokens)")
+                         "(token-budget profile), linear (linear layers against the number of tokens), decode_probe (what bounds the decode "
+                         "path: equal-length and mixed-length decode batches at one and two blocks per compute unit)")
     ap.add_argument("--seed", type=int, default=None, help="seed of the workload recipe (default: the recipe's own)")
     ap.add_argument("--copies", type=int, default=0, help="independent KV-pool/Q copies rotated between steps (0 = auto)")
     ap.add_argument("--values", choices=["normal", "zeros"], default="normal",
@@ -303,7 +370,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     from paper_2403_02310_amd import binding, harness
 
-    if args.values == "zeros" and args.workload in ("c5_sweep", "serve", "budget"):
+    if args.values == "zeros" and args.workload in ("c5_sweep", "serve", "budget", "decode_probe"):
         sys.stderr.write("bench.py: --values zeros applies to the single-batch workloads and to --workload linear\n")
         return 2
     if args.workload == "c5_sweep":
@@ -314,6 +381,8 @@ def main() -> int:
         return run_token_budget(args)
     if args.workload == "linear":
         return run_linear(args)
+    if args.workload == "decode_probe":
+        return run_decode_probe(args)
     batch, desc = make_workload(args.workload, args.seed)
     s = batch.shape
     T, S = batch.num_tokens, batch.num_seqs
