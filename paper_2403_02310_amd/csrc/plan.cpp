@@ -201,7 +201,12 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     // A wave-tile unit is a BLOCK: its four wavefronts take a quarter of the unit's keys each and
     // merge their results in LDS, so a unit of up to 4 x 1024 keys (6144 with the 1.5x allowance
     // below) needs no partial rows and no merge kernel; "split_keys" counts keys per wavefront.
-    const int64_t wave_floor = 4 * kMinWaveKeys;
+    // When the decodes of the batch take long to stream as a whole, one block may take longer too: a unit that
+    // needs up to 0.4 of that time (a block streams about 25 GB/s next to a second one on its compute unit) is
+    // dealt out first and is done well before the launch ends, and every cut avoided saves partial rows and,
+    // for a batch without other cuts, the merge launch.
+    const double wave_stream_us = (double)keys_of_kind[kKindWave] * cfg.num_kv_heads * cfg.head_dim * 4.0 / 5.0e6;
+    const int64_t wave_floor = std::max<int64_t>(4 * kMinWaveKeys, (int64_t)(0.4 * wave_stream_us * 25000.0 / (cfg.head_dim * 4.0)));
     int64_t wave_split = pick(4 * opt.split_keys, keys_of_kind[kKindWave], std::max<int64_t>(1, opt.target_items / 4), wave_floor);
     // Chunk tiles: enough units per KV head to put two blocks on every compute unit (a block
     // alone on its unit cannot hide its per-step latencies), but never pieces below the floor.
@@ -213,7 +218,7 @@ void plan_attention(const sarathi_config &cfg, const Options &opt, const Workspa
     const bool has_wave_tiles = plan.tiles.size() > n_chunk_tiles;
     int64_t tile_floor = kMinTileSplitKeys;
     if (has_wave_tiles) {
-        const double wave_us = (double)keys_of_kind[kKindWave] * cfg.num_kv_heads * cfg.head_dim * 4.0 / 5.0e6;
+        const double wave_us = wave_stream_us;
         tile_floor = std::max<int64_t>(2 * kMinTileSplitKeys, (int64_t)(wave_us / 1.2) * kTileKeys);
     }
     int64_t tile_split = pick(opt.tile_split_keys, keys_of_kind[kKindTile], tile_units_wanted, tile_floor);
