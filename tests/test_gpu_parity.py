@@ -143,6 +143,46 @@ def test_small_decode_batches_at_one_and_two_blocks_per_unit(hx):
     np.testing.assert_array_equal(outs[0], outs[2])
 
 
+RANDOM_SHAPES = [wl.AttnShape(4, 1, 64), wl.AttnShape(8, 2, 128), wl.AttnShape(14, 2, 128), wl.AttnShape(3, 3, 64),
+                 wl.AttnShape(20, 1, 128), wl.AttnShape(32, 8, 128), wl.AttnShape(8, 8, 64), wl.AttnShape(56, 8, 128),
+                 wl.AttnShape(12, 4, 64)]
+RANDOM_OPTIONS = [{}, {}, {"tile_split_keys": 64, "split_keys": 32}, {"tile_split_keys": 128}, {"split_keys": 64},
+                  {"interleave": 0}, {"interleave": 1}, {"interleave": 2, "resident_chunks": 1}, {"decode_blocks_per_cu": 1},
+                  {"decode_blocks_per_cu": 2}, {"tile_min_cols": 1}, {"tile_min_cols": 1 << 20}, {"window": 64},
+                  {"window": 333}, {"window": 1000, "tile_split_keys": 96}, {"inline_append": 0}, {"stream_kv": 0},
+                  {"stream_kv": 1}]
+
+
+def test_randomized_batches_shapes_and_options(hx):
+    """100 seeded draws of (head shape, number and size of chunks, number of decodes, longest context, planner and
+    launch options, sliding window): every output row against the checker.  Covers combinations the hand-picked
+    cases above do not (e.g. a windowed batch that is cut every 96 keys, decode-only launches forced to either
+    occupancy, chunk-only batches, contexts long enough to be cut across blocks)."""
+    rng = np.random.default_rng(20240310)
+    worst = [0.0, 0.0]
+    for case in range(100):
+        shape = RANDOM_SHAPES[int(rng.integers(len(RANDOM_SHAPES)))]
+        opts = RANDOM_OPTIONS[int(rng.integers(len(RANDOM_OPTIONS)))]
+        n_chunks = int(rng.integers(0, 5))
+        n_dec = int(rng.integers(0 if n_chunks else 1, 40))
+        max_ctx = int(rng.choice([60, 400, 1500, 4000, 9000]))
+        max_chunk = min(int(rng.choice([8, 40, 130, 300, 700])), max_ctx)
+        print("case", case, shape, "chunks", n_chunks, "decodes", n_dec, "max_chunk", max_chunk, "max_ctx", max_ctx, opts, flush=True)
+        b = wl.random_hybrid(9000 + case, shape, n_chunks, n_dec, max_chunk=max_chunk, max_ctx=max_ctx)
+        h = hx.make_handle(b)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        st = hx.setup_and_run(b, 0x7FC1, handle=h)
+        got = hx.bf16_tensor_to_f64(st["out"])
+        k_all = np.concatenate([st["kv_host"][i][0] for i in range(b.num_seqs)])
+        v_all = np.concatenate([st["kv_host"][i][1] for i in range(b.num_seqs)])
+        ref = oracle.hybrid_attention(b.q_bits(0), k_all, v_all, b.kv_start, b.q_start, b.q_len, b.ctx_len, b.sm_scale,
+                                      window=opts.get("window", 0))
+        res = compare(got, ref, "random case %d" % case)
+        worst = [max(worst[0], res[0]), max(worst[1], res[1])]
+    print("worst max abs %.3e, worst row rel %.3e" % tuple(worst), flush=True)
+
+
 @pytest.mark.parametrize("shape", ["gqa4_d128", "gqa7_d128", "mqa4_d64"])
 @pytest.mark.parametrize("window", [1, 17, 64, 300])
 def test_sliding_window(hx, shape, window):
