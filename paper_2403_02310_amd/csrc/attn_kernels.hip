@@ -69,6 +69,7 @@ namespace sarathi {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -569,7 +570,7 @@ __device__ __forceinline__ void chunk_step(ChunkState<D> &st, const bf16x8 (&qre
     f32x16 &s_next = SWAP ? st.s[OUT] : s_tmp;
     const f32x16 &s_cur = st.s[PP];
     const bf16x8 p_old0 = st.p[PP][0], p_old1 = st.p[PP][1];
-    typedef __attribute__((ext_vector_type(2))) float f32x2;
+
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     uint32_t p_new[8];  // bf16 pairs of the current tile's weights: registers (2k, 2k+1)
     float e_even = 0.f;
@@ -1110,17 +1111,43 @@ __global__ __launch_bounds__(kMergeCols * D / 4) void splitkv_reduce_kernel(Redu
     const int64_t split_stride = (int64_t)it.n_cols * p.num_kv_heads;
     const float *__restrict__ ml = p.part_ml;
     const float *__restrict__ po = p.part_o;
+    // Loads first, arithmetic after: the pieces' rows were written by the attention launch and come from memory,
+    // so a loop that loads, waits and accumulates piece by piece costs one memory latency per piece (and one more
+    // per piece for the maxima).  Up to kBatch pieces are fetched at once (indices beyond the last piece are clamped
+    // to it: a valid, unused read); the sums still run in index order.
+    constexpr int kBatch = 4;
+    const int n = it.n_splits;
+    float m[kBatch], l[kBatch];
+    f32x4 o[kBatch];
+    auto fetch = [&](int base) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int64_t prow = prow0 + (int64_t)min(base + j, n - 1) * split_stride;
+            const f32x2 v = *reinterpret_cast<const f32x2 *>(ml + prow * 2);
+            m[j] = v[0];
+            l[j] = v[1];
+            o[j] = *reinterpret_cast<const f32x4 *>(po + prow * D + d4);
+        }
+    };
+    fetch(0);
     float m_max = kNegSentinel;
-#pragma unroll 8
-    for (int i = 0; i < it.n_splits; ++i) m_max = fmaxf(m_max, ml[(prow0 + i * split_stride) * 2]);
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) m_max = fmaxf(m_max, m[j]);  // clamped entries repeat a valid piece
+    for (int i = kBatch; i < n; ++i) m_max = fmaxf(m_max, ml[(prow0 + i * split_stride) * 2]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < it.n_splits; ++i) {
-        const int64_t prow = prow0 + i * split_stride;
-        const float w = __builtin_amdgcn_exp2f(ml[prow * 2] - m_max);
-        lsum += w * ml[prow * 2 + 1];
-        acc += *reinterpret_cast<const f32x4 *>(po + prow * D + d4) * w;
+    for (int base = 0;;) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (base + j < n) {
+                const float w = __builtin_amdgcn_exp2f(m[j] - m_max);
+                lsum += w * l[j];
+                acc += o[j] * w;
+            }
+        }
+        base += kBatch;
+        if (base >= n) break;
+        fetch(base);
     }
     const bf16x4 o4 = __builtin_convertvector(acc * (1.0f / lsum), bf16x4);
     uint16_t *op = p.out + ((int64_t)(it.q_start + row) * p.num_q_heads + head) * D + d4;

@@ -261,7 +261,16 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(const float *part, u
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= elems) return;
     lf32x4 sum = *reinterpret_cast<const lf32x4 *>(part + i);
-    for (int s = 1; s < splits; ++s) sum += *reinterpret_cast<const lf32x4 *>(part + (int64_t)s * elems + i);
+    // four pieces are fetched before any is added (one memory latency per four pieces instead of one per piece;
+    // indices past the last piece are clamped to it and not added); the additions keep the piece order
+    for (int s = 1; s < splits; s += 4) {
+        lf32x4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = *reinterpret_cast<const lf32x4 *>(part + (int64_t)min(s + j, splits - 1) * elems + i);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (s + j < splits) sum += v[j];
+    }
     *reinterpret_cast<lu32x2 *>(y + i) = __builtin_bit_cast(lu32x2, __builtin_convertvector(sum, lbf16x4));
 }
 
