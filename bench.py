@@ -29,10 +29,10 @@ if ROOT not in sys.path:
 # recipe's own seed and the library's default options: a run with another seed, other options or other
 # values reports no traffic (null) rather than somebody else's.
 MEASURED_TRAFFIC_BYTES = {"c2": (606.4e6, "profiles/attention_c2_mistral_hybrid.md"),
-                          "c3": (1480.7e6, "profiles/attn_wave_kernel_c3_decode_only.md"),
-                          "c4": (5212.8e6, "profiles/attention_c4_yi_long.md"),
-                          "c4_chunks": (345.2e6, "profiles/attn_chunk_kernel_c4_chunks.md"),
-                          "c5": (9672.5e6, "profiles/attention_c5_llama70b.md")}
+                          "c3": (1480.8e6, "profiles/attn_wave_kernel_c3_decode_only.md"),
+                          "c4": (5149.7e6, "profiles/attention_c4_yi_long.md"),
+                          "c4_chunks": (345.9e6, "profiles/attn_chunk_kernel_c4_chunks.md"),
+                          "c5": (9673.0e6, "profiles/attention_c5_llama70b.md")}
 
 
 def measured_traffic(args):
