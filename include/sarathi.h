@@ -206,6 +206,9 @@ sarathi_status sarathi_hybrid_attention(sarathi_handle *handle,
  * handles, two threads) race; calls ordered by one stream are safe.  What must start at zero (the scheduling
  * words) is cleared by a fill kernel inside the call.  Results agree with sarathi_hybrid_attention's within the
  * attention tolerance, and bit for bit when no key range is cut differently.
+ * Under stream capture: make one call on the device before capturing (the first call on a device looks up the
+ * array's address); a captured call holds its plan in the captured kernel arguments, so a replay repeats the
+ * batch lengths it was captured with, on whatever the buffers then contain.
  */
 sarathi_status sarathi_hybrid_attention_noalloc(sarathi_handle *handle,
                                                 const void *q,

@@ -75,3 +75,46 @@ def test_noalloc_refuses_what_its_scratch_cannot_hold():
         h.hybrid_attention_noalloc(q, kc, kc, bt, q_start, q_len, ctx, 0.1, torch.empty_like(q))
     assert e.value.status == binding.ECAPACITY and "allocation-free" in str(e.value)
     torch.cuda.synchronize()
+
+
+def test_noalloc_captured_in_a_graph_and_replayed():
+    """What the entry point is for: a caller under stream capture.  One call is captured (kernels only: the plan
+    travels in kernel arguments, the scheduling words are cleared by a fill kernel), then replayed four times with
+    new queries of the same lengths, the program's own eager calls and synchronisations in between; every replay
+    equals the eager call bit for bit."""
+    from paper_2403_02310_amd import harness as hx
+    s = wl.AttnShape(8, 2, 128)
+    cases = ((wl._make("graph_big", s, [300, 1, 37, 1, 1, 200], [1300, 555, 37, 1, 7000, 900], 93), {"resident_chunks": 1}),
+             (wl.decodes_first(wl.config2_mistral_hybrid()), {}))
+    for batch, opts in cases:
+        print("case", batch.name, "options", opts, flush=True)
+        h = hx.make_handle(batch)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        st = hx.setup_and_run(batch, 0x7FC1, handle=h)
+        q = st["q"]
+        out_eager = torch.empty_like(st["out"])
+        out_graph = torch.full_like(st["out"], float("nan"))
+        rest = (st["k_cache"], st["v_cache"], st["bt"], batch.q_start, batch.q_len, batch.ctx_len, batch.sm_scale)
+        h.hybrid_attention_noalloc(q, *rest, out_eager)   # first use of the built-in scratch on this device, outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            h.hybrid_attention_noalloc(q, *rest, out_graph)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            q.copy_(hx.bits_to_device(batch.q_bits(rep)))
+            torch.cuda.synchronize()
+            h.hybrid_attention_noalloc(q, *rest, out_eager)
+            torch.cuda.synchronize()
+            out_graph.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(hx.device_to_bits(out_graph), hx.device_to_bits(out_eager))
+        compare(hx.bf16_tensor_to_f64(out_graph), _oracle_for_queries(batch, st, 3), batch.name + " last replay vs checker")
+
+
+def _oracle_for_queries(batch, st, q_copy):
+    k = np.concatenate([st["kv_host"][i][0] for i in range(batch.num_seqs)])
+    v = np.concatenate([st["kv_host"][i][1] for i in range(batch.num_seqs)])
+    return oracle.hybrid_attention(batch.q_bits(q_copy), k, v, batch.kv_start, batch.q_start, batch.q_len, batch.ctx_len, batch.sm_scale)
