@@ -45,6 +45,9 @@ def measured_traffic(args):
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+# What a decode-only launch of identical decodes streams on this part (`--workload decode_probe`, 512 blocks and more;
+# profiles/decode_streaming_rate_probes.md): the ceiling of this access pattern, reported beside the published peak.
+MEASURED_STREAMING_CEILING_GBS = 6650.0
 
 
 def make_workload(name: str, seed=None):
@@ -570,7 +573,9 @@ def main() -> int:
         else:
             ach = alg_bytes / (kern_us * 1e-6) / 1e9
             result["roofline"] = {"bound": "hbm", "kernel": attn_kernel, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                                  "traffic": traffic, "traffic_source": traffic_src, "duration_us": kern_us}
+                                  "traffic": traffic, "traffic_source": traffic_src, "duration_us": kern_us,
+                                  "measured_streaming_ceiling": {"GBps": MEASURED_STREAMING_CEILING_GBS, "frac": ach / MEASURED_STREAMING_CEILING_GBS,
+                                                                 "source": "profiles/decode_streaming_rate_probes.md"}}
 
     # ---- CPU baseline: the fp64 checker as it stands, on the host cores, bounded sample ----
     if not args.no_cpu_baseline:
