@@ -131,6 +131,21 @@ def test_plan_coverage_under_a_sliding_window(window):
     _coverage_check(wl.config4_yi_long(), window=window)
 
 
+def test_long_decodes_are_cut_only_where_their_block_would_be_the_tail():
+    """A decode's keys go to one block of four wavefronts unless that block would outlast a good part of the time
+    the batch's decodes take to stream: the 16,384-key decodes of the long-context recipe stay whole (no partial
+    rows, no merge launch), the same decode next to a handful of short ones is cut, and so is a lone long decode."""
+    info = _coverage_check(wl.config4_yi_long())
+    assert info.num_reduce_items == 0 and info.num_part_rows == 0
+    s = wl.AttnShape(56, 8, 128)
+    few = wl._make("few", s, [1] * 6, [16384, 300, 900, 50, 1200, 700], 10)
+    info = _coverage_check(few)
+    assert info.num_reduce_items == 1 and info.num_part_rows > 0          # only the long one, in several pieces
+    lone = wl._make("lone", s, [1], [100000], 11)
+    info = _coverage_check(lone)
+    assert info.num_reduce_items == 1 and info.num_items >= 8
+
+
 def test_plan_stays_within_the_workspace_when_everything_is_long():
     s = wl.AttnShape(64, 8, 128)
     b = wl._make("long", s, [2048], [16384], 9)
