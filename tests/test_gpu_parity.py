@@ -143,6 +143,17 @@ def test_small_decode_batches_at_one_and_two_blocks_per_unit(hx):
     np.testing.assert_array_equal(outs[0], outs[2])
 
 
+def test_very_long_contexts(hx):
+    """A decode over 131,072 keys (8,192 pages: cut across blocks, partial rows, merge), a 96-row chunk behind a
+    100,000-token prefix (chunk tiles cut for balance) and a short decode in one batch: page and key offsets far
+    beyond what the recipes reach."""
+    s = wl.AttnShape(8, 2, 128)
+    b = wl._make("very_long", s, [1, 96, 1], [131072, 100096, 77], 81, slack=1.05)
+    st, got, ref, _ = _check_batch(hx, b, check_pools=False)
+    info, items = st["handle"].plan(b.q_start, b.q_len, b.ctx_len)
+    assert info.num_reduce_items >= 2 and max(it.key_end for it in items) == 131072
+
+
 RANDOM_SHAPES = [wl.AttnShape(4, 1, 64), wl.AttnShape(8, 2, 128), wl.AttnShape(14, 2, 128), wl.AttnShape(3, 3, 64),
                  wl.AttnShape(20, 1, 128), wl.AttnShape(32, 8, 128), wl.AttnShape(8, 8, 64), wl.AttnShape(56, 8, 128),
                  wl.AttnShape(12, 4, 64)]
