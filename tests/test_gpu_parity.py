@@ -154,6 +154,21 @@ def test_very_long_contexts(hx):
     assert info.num_reduce_items >= 2 and max(it.key_end for it in items) == 131072
 
 
+@pytest.mark.parametrize("heads", [(32, 32, 128), (64, 16, 64), (40, 40, 64)])
+def test_many_kv_heads(hx, heads):
+    """Shapes with many KV heads (multi-head attention with as many KV heads as query heads; more KV heads than the
+    part has XCDs): default launch, run-time roles asked for, forced cuts, two kernels in sequence."""
+    s = wl.AttnShape(*heads)
+    b = wl._make("kvh%d" % heads[1], s, [130, 1, 1, 20, 1], [700, 300, 1, 20, 2500], 82)
+    _, _, ref, _ = _check_batch(hx, b, check_pools=True)
+    for opts in ({"resident_chunks": 1}, {"tile_split_keys": 64, "split_keys": 64}, {"interleave": 0}):
+        h = hx.make_handle(b)
+        for k, v in opts.items():
+            h.set_option(k, v)
+        print("options", opts, flush=True)
+        compare(hx.bf16_tensor_to_f64(hx.setup_and_run(b, 0x7FC1, handle=h)["out"]), ref, str(opts))
+
+
 RANDOM_SHAPES = [wl.AttnShape(4, 1, 64), wl.AttnShape(8, 2, 128), wl.AttnShape(14, 2, 128), wl.AttnShape(3, 3, 64),
                  wl.AttnShape(20, 1, 128), wl.AttnShape(32, 8, 128), wl.AttnShape(8, 8, 64), wl.AttnShape(56, 8, 128),
                  wl.AttnShape(12, 4, 64)]
